@@ -1,0 +1,306 @@
+"""Pins for the CPU checker: each test holds it to something fixed outside of it (published
+known answers, exhaustive enumeration, closed forms, textbook special cases, invariants)."""
+import itertools
+import math
+import os
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_29346_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------- random source
+def test_philox_known_answers(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        assert oracle.philox4x32_10(v[0:4], v[4:6]) == v[6:10]
+
+
+def test_mulhi64_is_floor_of_product_over_2_64(oracle):
+    rnd = random.Random(1)
+    cases = [(0, 0), (2**64 - 1, 2**64 - 1), (2**63, 2), (2**32, 2**32), (2**64 - 1, 1), (1, 2**64 - 1)]
+    cases += [(rnd.getrandbits(64), rnd.getrandbits(64)) for _ in range(2000)]
+    cases += [(rnd.getrandbits(64), rnd.randrange(1, 300000)) for _ in range(2000)]
+    for a, b in cases:
+        assert oracle.mulhi64(a, b) == (a * b) >> 64
+
+
+def test_draw_is_keyed_by_key_hop_node_slot(oracle):
+    # the draw is the first two Philox words for counter (node, slot, hop, 0) and key (low, high)
+    rnd = random.Random(2)
+    for _ in range(200):
+        key, hop, node, slot = rnd.getrandbits(64), rnd.randrange(8), rnd.randrange(2**31), rnd.randrange(64)
+        w = oracle.philox4x32_10([node, slot, hop, 0], [key & 0xFFFFFFFF, key >> 32])
+        assert oracle.draw(key, hop, node, slot) == w[0] | (w[1] << 32)
+    # each of the four coordinates matters
+    base = oracle.draw(5, 1, 7, 3)
+    assert len({base, oracle.draw(6, 1, 7, 3), oracle.draw(5, 2, 7, 3), oracle.draw(5, 1, 8, 3),
+                oracle.draw(5, 1, 7, 4), oracle.draw(5 + 2**32, 1, 7, 3)}) == 6
+
+
+# ---------------------------------------------------------------------------- Floyd subsets
+@pytest.mark.parametrize("deg,F", [(5, 3), (6, 2), (4, 3), (7, 4), (3, 1), (6, 5)])
+def test_floyd_resolution_is_exactly_uniform_over_subsets(oracle, deg, F):
+    # enumerate every candidate sequence t_j in [0, deg-F+j]: each F-subset must come up equally often
+    ranges = [range(deg - F + j + 1) for j in range(F)]
+    counts = {}
+    total = 0
+    for t in itertools.product(*ranges):
+        pos = oracle.floyd_resolve(deg, F, list(t))
+        assert len(set(pos)) == F and all(0 <= p < deg for p in pos)
+        key = frozenset(pos)
+        counts[key] = counts.get(key, 0) + 1
+        total += 1
+    assert len(counts) == math.comb(deg, F)
+    assert set(counts.values()) == {total // math.comb(deg, F)}
+
+
+def test_sample_positions_counts_and_take_all(oracle):
+    for deg in range(0, 12):
+        for F in range(1, 8):
+            pos = oracle.sample_positions(99, 0, 1234, deg, F)
+            assert len(pos) == min(F, deg)
+            assert len(set(pos)) == len(pos) and all(0 <= p < deg for p in pos)
+            if deg <= F:
+                assert pos == list(range(deg))  # whole row, CSR order, no draw involved
+            posr = oracle.sample_positions(99, 0, 1234, deg, F, with_replacement=True)
+            assert len(posr) == (F if deg > 0 else 0) and all(0 <= p < deg for p in posr)
+
+
+def test_sampled_subsets_are_uniform_over_keys(oracle):
+    # deg=8, F=3: 56 subsets; 56000 keys -> chi-square with 55 degrees of freedom (99.99% point ~ 106)
+    deg, F, N = 8, 3, 56000
+    counts = {}
+    first = np.zeros(deg)
+    for key in range(N):
+        pos = oracle.sample_positions(0xABCDEF0000 + key, 1, 4242, deg, F)
+        counts[frozenset(pos)] = counts.get(frozenset(pos), 0) + 1
+        for p in pos:
+            first[p] += 1
+    assert len(counts) == 56
+    exp = N / 56
+    chi2 = sum((c - exp) ** 2 / exp for c in counts.values())
+    assert chi2 < 106, chi2
+    # every position, the last one included, is hit with probability F/deg
+    assert np.all(np.abs(first / N - F / deg) < 0.01)
+
+
+def test_with_replacement_positions_are_uniform(oracle):
+    deg, F, N = 7, 4, 20000
+    hist = np.zeros(deg)
+    for key in range(N):
+        for p in oracle.sample_positions(key * 7919 + 1, 0, 17, deg, F, with_replacement=True):
+            hist[p] += 1
+    exp = N * F / deg
+    chi2 = float(((hist - exp) ** 2 / exp).sum())
+    assert chi2 < 27.9, chi2  # 6 dof, 99.99% point
+
+
+def test_positions_follow_the_candidate_rule(oracle):
+    # t_j = floor(x_j * (deg-F+j+1) / 2^64) fed through the (exhaustively checked) resolution
+    rnd = random.Random(3)
+    for _ in range(300):
+        key, hop, node = rnd.getrandbits(64), rnd.randrange(4), rnd.randrange(10**6)
+        F = rnd.randrange(1, 26)
+        deg = F + rnd.randrange(1, 5000)
+        t = [(oracle.draw(key, hop, node, j) * (deg - F + j + 1)) >> 64 for j in range(F)]
+        assert oracle.sample_positions(key, hop, node, deg, F) == oracle.floyd_resolve(deg, F, t)
+
+
+# ---------------------------------------------------------------------------- whole pipeline
+def _np_graph(oracle, g):
+    return oracle.Graph(g.offsets.numpy(), g.indices.numpy())
+
+
+def _check_invariants(g, og, seeds, fanouts, b, replace=False):
+    off = og.offsets
+    idx = og.indices
+    H = len(fanouts)
+    assert b.n[0] == len(seeds) and np.array_equal(b.S[: b.n[0]], seeds)
+    for h in range(H):
+        n, F = b.n[h], fanouts[h]
+        D = b.S[:n]
+        rp, nb, col = b.row_ptr[h], b.nbr_gid[h], b.col[h]
+        deg = (off[D.astype(np.int64) + 1] - off[D.astype(np.int64)]).astype(np.int64)
+        k = np.where(deg > 0, F, 0) if replace else np.minimum(deg, F)
+        assert rp[0] == 0 and np.array_equal(np.diff(rp), k) and rp[-1] == b.E[h] == len(nb) == len(col)
+        assert b.E[h] <= n * F
+        for i in range(n):
+            row = idx[off[D[i]]: off[D[i] + 1]]
+            got = nb[rp[i]: rp[i + 1]]
+            assert np.all(np.isin(got, row)), "sampled id is not a neighbor"
+            if not replace:
+                assert len(np.unique(got)) == len(got), "duplicate within a row (rows are duplicate-free)"
+                if deg[i] <= F:
+                    assert np.array_equal(got, row)
+        n2 = b.n[h + 1]
+        S = b.S[:n2]
+        assert len(np.unique(S)) == n2, "S_h has duplicates"
+        tail = S[n:]
+        assert np.all(np.diff(tail) > 0), "new vertices not ascending"
+        assert not np.any(np.isin(tail, D))
+        assert set(S.tolist()) == set(D.tolist()) | set(nb.tolist())
+        # definition of S_h: D_h ++ sorted(new)
+        assert np.array_equal(tail, np.array(sorted(set(nb.tolist()) - set(D.tolist())), dtype=np.int32))
+        assert np.all((col >= 0) & (col < n2)) and np.array_equal(S[col], nb)
+        assert np.all(np.isin(np.arange(n, n2), col)), "a new local id is never referenced"
+
+
+@pytest.mark.parametrize("replace", [False, True])
+def test_pipeline_invariants_tiny_config(oracle, replace):
+    cfg = W.CONFIGS["tiny"]
+    g = cfg.build_graph()
+    assert g.num_nodes == 10_000 and g.num_edges == 100_000 and g.offsets.dtype == torch.int32
+    og = _np_graph(oracle, g)
+    seeds = cfg.seed_pool(g).batch_for(0).numpy()
+    assert len(seeds) == 64 and len(set(seeds.tolist())) == 64
+    b = og.sample_blocks(seeds, cfg.fanouts, cfg.key_for(0), with_replacement=replace)
+    _check_invariants(g, og, seeds, cfg.fanouts, b, replace)
+    # Eq. 1 applied hop by hop: n_{h+1} <= n_h (1 + F_h), capped by |V|
+    for h, F in enumerate(cfg.fanouts):
+        assert b.n[h + 1] <= min(g.num_nodes, b.n[h] * (1 + F))
+
+
+@pytest.mark.parametrize("seed,fanouts,i64", [(1, (3,), False), (2, (4, 2), True), (3, (2, 3, 2), True), (4, (7, 1), False)])
+def test_pipeline_invariants_random_small(oracle, seed, fanouts, i64):
+    g = W.rmat_graph(700, 9000, seed, offsets_dtype=torch.int64 if i64 else torch.int32)
+    og = _np_graph(oracle, g)
+    rnd = np.random.RandomState(seed)
+    seeds = rnd.permutation(g.num_nodes)[:37].astype(np.int32)
+    for replace in (False, True):
+        b = og.sample_blocks(seeds, fanouts, 1000 + seed, with_replacement=replace)
+        _check_invariants(g, og, seeds, fanouts, b, replace)
+
+
+def test_determinism_and_key_sensitivity(oracle):
+    g = W.rmat_graph(2000, 60000, 11)
+    og = _np_graph(oracle, g)
+    seeds = np.arange(100, 164, dtype=np.int32)
+    a = og.sample_blocks(seeds, (5, 5), 42)
+    b = og.sample_blocks(seeds, (5, 5), 42)
+    c = og.sample_blocks(seeds, (5, 5), 43)
+    assert np.array_equal(a.S, b.S) and all(np.array_equal(x, y) for x, y in zip(a.nbr_gid, b.nbr_gid))
+    assert not np.array_equal(a.nbr_gid[0], c.nbr_gid[0])
+    # the hop index enters the draw: the same vertex sampled at hop 0 and hop 1 gets different subsets
+    deg = np.diff(og.offsets)
+    v = int(np.argmax(deg))
+    one = og.sample_blocks(np.array([v], dtype=np.int32), (5, 5), 42)
+    assert not np.array_equal(one.nbr_gid[0][:5], one.nbr_gid[1][:5])
+
+
+def test_invalid_seeds_are_rejected(oracle):
+    g = W.rmat_graph(500, 4000, 5)
+    og = _np_graph(oracle, g)
+    with pytest.raises(ValueError):
+        og.sample_blocks(np.array([1, 2, 2], dtype=np.int32), (2,), 1)
+    with pytest.raises(ValueError):
+        og.sample_blocks(np.array([1, 500], dtype=np.int32), (2,), 1)
+    with pytest.raises(ValueError):
+        og.sample_blocks(np.array([-1], dtype=np.int32), (2,), 1)
+
+
+def test_full_neighborhood_is_bfs_ball_and_normalised_adjacency_product(oracle):
+    # fanout >= max degree: no randomness left; S_h is the BFS ball and the mean aggregation is the
+    # row-normalised adjacency matrix times the features (dense textbook computation)
+    nn = 60
+    rnd = np.random.RandomState(7)
+    A = (rnd.rand(nn, nn) < 0.08).astype(np.float64)
+    A[5, :] = 0  # a vertex with no neighbors
+    off = np.concatenate([[0], np.cumsum(A.sum(1))]).astype(np.int32)
+    idx = np.concatenate([np.nonzero(A[v])[0] for v in range(nn)]).astype(np.int32)
+    og = oracle.Graph(off, idx)
+    F = int(A.sum(1).max()) + 1
+    seeds = np.array([3, 5, 17, 40], dtype=np.int32)
+    feat = rnd.randn(nn, 6).astype(np.float32)
+    for key in (1, 2):
+        blocks, X, agg = oracle.step(og, seeds, (F, F), key, feat)
+        ball = set(seeds.tolist())
+        for h in range(2):
+            D = blocks.S[: blocks.n[h]]
+            assert set(D.tolist()) == ball
+            nxt = set(ball)
+            for v in ball:
+                nxt |= set(np.nonzero(A[v])[0].tolist())
+            ball = nxt
+            assert set(blocks.S[: blocks.n[h + 1]].tolist()) == ball
+            # block h as a dense matrix equals the rows of A restricted to D_h
+            dense = np.zeros((blocks.n[h], nn))
+            for i in range(blocks.n[h]):
+                for e in range(blocks.row_ptr[h][i], blocks.row_ptr[h][i + 1]):
+                    dense[i, blocks.S[blocks.col[h][e]]] += 1
+            assert np.array_equal(dense, A[D])
+        assert np.array_equal(X, feat[blocks.S])
+        D1 = blocks.S[: blocks.n[1]]
+        degs = A[D1].sum(1, keepdims=True)
+        expect = np.where(degs > 0, (A[D1] @ feat.astype(np.float64)) / np.maximum(degs, 1), 0.0)
+        np.testing.assert_allclose(agg, expect, rtol=1e-6, atol=1e-7)
+        assert np.all(agg[degs[:, 0] == 0] == 0)
+
+
+def test_gather_and_mean_special_features(oracle):
+    cfg = W.CONFIGS["tiny"]
+    g = cfg.build_graph()
+    og = _np_graph(oracle, g)
+    seeds = cfg.seed_pool(g).batch_for(0).numpy()
+    nn = g.num_nodes
+    # column 0 = vertex id, column 1 = 1, column 2 = -2 * id
+    feat = np.stack([np.arange(nn), np.ones(nn), -2.0 * np.arange(nn)], 1).astype(np.float32)
+    blocks, X, agg = oracle.step(og, seeds, cfg.fanouts, 9, feat)
+    assert np.array_equal(X[:, 0].astype(np.int64), blocks.S)
+    rp, col, nb = blocks.row_ptr[-1], blocks.col[-1], blocks.nbr_gid[-1]
+    k = np.diff(rp)
+    assert agg.shape == (blocks.n[-2], 3)
+    assert np.all(agg[k > 0, 1] == 1.0) and np.all(agg[k == 0] == 0.0)
+    sums = np.array([nb[rp[i]: rp[i + 1]].astype(np.int64).sum() for i in range(len(k))])
+    np.testing.assert_allclose(agg[:, 0].astype(np.float64) * k, sums, rtol=1e-6)
+    np.testing.assert_allclose(agg[:, 2].astype(np.float64) * k, -2.0 * sums, rtol=1e-6)
+
+
+def test_mean_against_numpy_segments(oracle):
+    rnd = np.random.RandomState(5)
+    n_in, n_out, dim = 300, 50, 9
+    k = rnd.randint(0, 12, size=n_out)
+    rp = np.concatenate([[0], np.cumsum(k)]).astype(np.int32)
+    col = rnd.randint(0, n_in, size=rp[-1]).astype(np.int32)
+    X = rnd.randn(n_in, dim).astype(np.float32)
+    out = oracle.aggregate_mean(rp, col, X)
+    for i in range(n_out):
+        seg = X[col[rp[i]: rp[i + 1]]].astype(np.float64)
+        exp = seg.mean(0) if k[i] else np.zeros(dim)
+        np.testing.assert_allclose(out[i], exp, rtol=1e-6, atol=1e-7)
+
+
+# ---------------------------------------------------------------------------- input generators
+def test_generators_are_deterministic_and_well_formed():
+    a = W.rmat_graph(3000, 40000, 21)
+    b = W.rmat_graph(3000, 40000, 21)
+    assert torch.equal(a.offsets, b.offsets) and torch.equal(a.indices, b.indices)
+    off, idx = a.offsets.numpy(), a.indices.numpy()
+    assert off[0] == 0 and off[-1] == len(idx) and np.all(np.diff(off) >= 0)
+    assert idx.min() >= 0 and idx.max() < 3000
+    for v in range(3000):
+        r = idx[off[v]: off[v + 1]]
+        assert np.all(np.diff(r) > 0)
+    deg = np.diff(off)
+    assert deg.max() > 20 * deg.mean(), "expected a heavy tail"
+    f = W.feature_table(2000, 16, 3)
+    assert abs(float(f.mean())) < 0.05 and abs(float(f.std()) - 1.0) < 0.05
+    assert torch.equal(W.feature_rows(torch.tensor([7, 1999, 0]), 16, 3), f[[7, 1999, 0]])
+    c = W.CONFIGS["envelope_stress"].scaled(0.004, batch=512)
+    g = c.build_graph()
+    off, idx = g.offsets.numpy(), g.indices.numpy()
+    # symmetric, with the designated hubs far above the average degree
+    keys = set(zip(np.repeat(np.arange(g.num_nodes), np.diff(off)).tolist(), idx.tolist()))
+    assert all((d, s) in keys for (s, d) in list(keys)[:2000])
+    assert np.diff(off)[g.hubs.numpy()].min() > 5 * np.diff(off).mean()
+    pool = c.seed_pool(g)
+    for s in range(5):
+        bt = pool.batch_for(s).numpy()
+        assert len(bt) == c.batch and len(set(bt.tolist())) == c.batch
