@@ -1,0 +1,188 @@
+/*
+ * zg - device-resident mini-batch construction for sampling-based GNN training on AMD MI355X.
+ *
+ * One training iteration's mini-batch construction (paper section 2.2): multi-hop neighbor
+ * sampling from a CSR graph, dedup + relabeling of every hop's vertex set, the hop's block
+ * CSR, the feature-row gather and a GraphSAGE mean aggregation.  Every count and offset the
+ * step produces stays in a device-resident metadata buffer (section 4.1); all kernels run with
+ * launch shapes fixed by a capacity envelope provisioned once (sections 4.2, 4.3) and read the
+ * true sizes on the device; the step is a captured hipGraph replayed without any host
+ * synchronisation (section 4.4).
+ *
+ * Conventions
+ *  - Plain C ABI.  Every function returns 0 (ZG_OK) or a negative zg_status; nothing throws.
+ *    zg_last_error() gives a thread-local message for the last failure.
+ *  - Pointers named d_* are DEVICE pointers (hipMalloc'ed or a torch CUDA tensor's data_ptr);
+ *    all others are HOST pointers.  The library borrows device memory, it never frees it, and
+ *    apart from zg_graph_create(ZG_GRAPH_VALIDATE) it never allocates any: the caller
+ *    provides one workspace whose size zg_plan_query reports.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - Hops h = 0..H-1 count outward from the seeds.  D_h (n_h vertices) is the frontier whose
+ *    neighbors hop h samples - the rows of block h; S_h = D_h followed by the hop's newly
+ *    discovered vertices in ascending global id - the columns of block h; D_{h+1} = S_h.
+ *    A vertex's local id is its index in S_{H-1}; every D_h and S_h is a prefix of that list.
+ *    (The paper names the mini-batch side of a hop the source set V_s and the sampled side the
+ *    destination set V_d.)
+ *  - fanouts[h] applies at hop h (fanouts[0] to the seeds).
+ */
+#ifndef ZG_H
+#define ZG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZG_MAX_HOPS 8
+#define ZG_MAX_FANOUT 64
+#define ZG_LOG_STRIDE 32 /* uint32 words per step in the device-side step log */
+
+typedef struct zg_graph_s zg_graph_t;
+typedef struct zg_plan_s zg_plan_t;
+
+enum zg_status { ZG_OK = 0, ZG_EINVAL = -1, ZG_ENOMEM = -2, ZG_EHIP = -3, ZG_ESTATE = -4 };
+enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
+
+/* zg_graph_create flags */
+#define ZG_GRAPH_VALIDATE 1u /* synchronising check: indices in range, rows ascending (hence duplicate-free) */
+
+/* zg_envelope.flags */
+#define ZG_PLAN_EAGER 1u   /* launch the step's kernels one by one instead of replaying a hipGraph */
+#define ZG_PLAN_REPLACE 2u /* sample with replacement (the setting of the paper's Lemma 1) */
+
+/* bits of the sticky device status word (zg_overflow_flag) */
+#define ZG_FLAG_HOP_OVERFLOW(h) (1u << (h)) /* |S_h| exceeded its cap at hop h: outputs of the step invalid */
+#define ZG_FLAG_SEED_RANGE (1u << 16)       /* a seed id outside [0, num_nodes) */
+#define ZG_FLAG_SEED_DUP (1u << 17)         /* the same seed twice */
+#define ZG_FLAG_INTERNAL (1u << 18)         /* a bounded device-side wait ran out (should never happen) */
+
+enum zg_env_mode {
+    ZG_ENV_MAX = 0,     /* worst case n_{h+1} = min(|V|, n_h (1 + F_h)): Eq. 1 applied hop by hop; never overflows */
+    ZG_ENV_MODEL = 1,   /* Lemma 1: Poisson-binomial mean/sigma of the deduplicated size, plus margin */
+    ZG_ENV_EXPLICIT = 2 /* caller's per-hop vertex caps (e.g. from a pilot run) */
+};
+
+/* Execution envelope request (section 4.3, "Metadata-Free Dispatcher"). */
+typedef struct {
+    int32_t mode;       /* zg_env_mode */
+    uint32_t flags;     /* ZG_PLAN_* */
+    double margin;      /* ZG_ENV_MODEL: relative head-room over the model mean; < 0 selects 0.20 (appendix B) */
+    double confidence;  /* ZG_ENV_MODEL: p of z = Phi^-1(p^(1/m)); <= 0 selects 0.9999 */
+    int64_t iterations; /* ZG_ENV_MODEL: m; <= 0 selects 1000 */
+    int64_t node_caps[ZG_MAX_HOPS + 1]; /* ZG_ENV_EXPLICIT: cap of n_h for h = 1..H ([0] ignored); clamped to the worst case */
+} zg_envelope;
+
+/* Host-side answer of zg_plan_query. */
+typedef struct {
+    int32_t num_hops;
+    int32_t feat_dim;
+    int64_t node_cap[ZG_MAX_HOPS + 1];    /* capacity of n_h, h = 0..H (node_cap[0] = batch) */
+    int64_t edge_cap[ZG_MAX_HOPS];        /* node_cap[h] * fanouts[h] (exact bound) */
+    int64_t maxsg_nodes[ZG_MAX_HOPS + 1]; /* worst case per hop (what ZG_ENV_MAX reserves) */
+    double model_mean[ZG_MAX_HOPS + 1];   /* Lemma 1 mean of n_h (0 when the graph has no degree statistics) */
+    double model_sigma[ZG_MAX_HOPS + 1];  /* Lemma 1 sigma of n_h */
+    double z;                             /* Phi^-1(confidence^(1/iterations)) */
+    int64_t envelope_bytes;               /* step outputs: S, block CSRs, X, agg, metadata */
+    int64_t scratch_bytes;                /* id map over |V|, bitmap, scan state */
+    int64_t workspace_bytes;              /* envelope + scratch + alignment: what zg_plan needs */
+    int64_t maxsg_envelope_bytes;         /* envelope_bytes if ZG_ENV_MAX had been used */
+    int32_t grid_sample[ZG_MAX_HOPS];     /* launch caps (workgroups) of the fixed launch skeleton */
+    int32_t grid_compact;
+    int32_t grid_relabel[ZG_MAX_HOPS];
+    int32_t grid_gather;
+    int32_t grid_aggregate;
+} zg_plan_info;
+
+/* Device addresses of a plan's outputs; fixed for the plan's lifetime (section 4.4, "stable buffers"). */
+typedef struct {
+    int32_t num_hops;
+    int32_t feat_dim;
+    const uint32_t *d_n;       /* [H+1] n_h of the last step */
+    const uint32_t *d_E;       /* [H]   sampled edges per hop */
+    const uint32_t *d_n_exact; /* [H+1] n_h before clamping to the cap */
+    const uint32_t *d_flags;   /* sticky status word */
+    const int32_t *d_S;        /* [node_cap[H]] global ids; local id = index */
+    const int32_t *d_row_ptr[ZG_MAX_HOPS]; /* [node_cap[h]+1] */
+    const int32_t *d_nbr_gid[ZG_MAX_HOPS]; /* [edge_cap[h]] sampled neighbor global ids, slot order */
+    const int32_t *d_col[ZG_MAX_HOPS];     /* [edge_cap[h]] local ids: block h is (row_ptr, col), n_h x n_{h+1} */
+    int64_t node_cap[ZG_MAX_HOPS + 1];
+    int64_t edge_cap[ZG_MAX_HOPS];
+    const float *d_X;   /* [node_cap[H], ldx] gathered feature rows of S_{H-1} (NULL if feat_dim == 0) */
+    int64_t ldx;
+    const float *d_agg; /* [node_cap[H-1], ld_agg] mean of block H-1 over X */
+    int64_t ld_agg;
+    const uint32_t *d_log; /* ring of ZG_LOG_STRIDE-word records, one per step: epoch, flags, n[0..H], E[0..H-1], n_exact[1..H] */
+    int32_t log_capacity;  /* records in the ring; record of step e sits at (e % log_capacity) */
+    const uint32_t *d_epoch; /* number of steps run on this plan */
+} zg_outputs;
+
+const char *zg_strerror(int status);
+const char *zg_last_error(void);
+
+/* ---- graph ------------------------------------------------------------------------------------
+ * CSR as in section 2.1: row v = the neighbor list that is sampled for v (direction is the caller's
+ * choice).  d_offsets: [num_nodes+1] int32 or int64 (offsets_dtype); d_indices: [num_edges] int32;
+ * num_nodes < 2^31, every degree < 2^31.  Both arrays are borrowed and must outlive the handle.
+ * Synchronises (init time): the offsets are read back once to collect the degree statistics the
+ * envelope model needs. */
+int zg_graph_create(zg_graph_t **g, int64_t num_nodes, int64_t num_edges, const void *d_offsets, int32_t offsets_dtype,
+                    const int32_t *d_indices, uint32_t flags);
+/* A handle that carries degree statistics only (host arrays: distinct degree values and how many
+ * vertices have each): enough for zg_plan_query / capacity planning on a machine with no GPU;
+ * zg_plan rejects it. */
+int zg_graph_create_stats(zg_graph_t **g, int64_t num_nodes, int64_t num_edges, const int64_t *degrees,
+                          const int64_t *counts, int64_t n_distinct);
+int zg_graph_destroy(zg_graph_t *g);
+/* Host pointers owned by the handle. */
+int zg_graph_degree_histogram(const zg_graph_t *g, int64_t *n_distinct, const int64_t **degrees, const int64_t **counts);
+
+/* ---- envelope model (host only; Lemma 1 and appendix A) -----------------------------------------
+ * Standard normal quantile Phi^-1(p), 0 < p < 1. */
+double zg_normal_quantile(double p);
+/* Mean and sigma of the deduplicated vertex count after each hop.  With pi_v = deg(v) / sum(deg) and
+ * S_h = expected number of neighbor draws up to and including hop h, a vertex is hit with probability
+ * p_v = 1 - (1 - pi_v)^{S_h}; mean[h+1] = batch + sum_v p_v, sigma^2 = sum_v p_v (1 - p_v); mean[0] =
+ * batch, sigma[0] = 0.  Draws of hop h: every vertex of D_h draws min(F_h, deg) (F_h if deg > 0 with
+ * replacement); seeds are uniform over V, later vertices are weighted by their hit probability. */
+int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_distinct, const int32_t *fanouts,
+                      int32_t num_hops, int32_t batch, int32_t with_replacement, double *mean, double *sigma);
+
+/* ---- plan -------------------------------------------------------------------------------------
+ * Host only.  Caps, launch caps and workspace size for (fanouts, batch, envelope, feat_dim);
+ * feat_dim = 0 plans the sampling/relabel/CSR part only.  1 <= fanouts[h] <= ZG_MAX_FANOUT. */
+int zg_plan_query(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
+                  int32_t feat_dim, zg_plan_info *out);
+/* Lays the metadata buffer and every step buffer out at fixed addresses inside d_workspace (256-byte
+ * aligned, >= workspace_bytes), initialises the scratch state on `stream` and builds the replayable
+ * launch skeleton.  May synchronise.  The workspace belongs to the plan until zg_plan_destroy. */
+int zg_plan(zg_plan_t **p, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+            const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream);
+int zg_plan_destroy(zg_plan_t *p);
+/* Makes gather + aggregation part of the step: d_feat is the [num_nodes, ld] fp32 table (row stride ld
+ * elements, >= feat_dim), borrowed.  Rebuilds the captured graph; call between steps, may synchronise. */
+int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld);
+int zg_plan_outputs(const zg_plan_t *p, zg_outputs *out);
+
+/* ---- per step ---------------------------------------------------------------------------------
+ * One mini-batch: d_seeds = `batch` distinct vertex ids (device memory, or pinned host memory the
+ * device can read), read when the step runs on `stream`.  Enqueues the ingest of (seeds, rng_key) and
+ * ONE graph launch; never synchronises, never allocates.  Results are in the plan's output buffers
+ * once `stream` reaches this point.  Steps of one plan must be stream-ordered one after another. */
+int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
+/* Stand-alone feature gather for the plan's current S_{H-1}: d_out[i,:] = d_feat[S[i],:], i < n_H;
+ * rows >= n_H of d_out are not written. */
+int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, void *stream);
+/* Stand-alone mean aggregation on block `hop` of the current step: d_out[i,:] = mean of d_in[col[e],:]
+ * over row i (0 for an empty row), i < n_hop. */
+int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
+                      int64_t ld_out, void *stream);
+/* Device address of the sticky status word (ZG_FLAG_*).  The caller reads it when it chooses. */
+int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag);
+int zg_overflow_clear(zg_plan_t *p, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,944 @@
+// HIP kernels (gfx950, wave64) and the plan / step entry points of libzg.
+//
+// One step = ingest, then per hop {sample, compact, relabel}, then gather, aggregate, finish.
+// Every kernel is launched with a grid fixed by the plan's capacity envelope, reads the true sizes
+// from the device-resident metadata buffer and lets surplus workgroups return at once (paper
+// sections 4.1-4.3).  Everything after the ingest is one hipGraph (section 4.4).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "zg_internal.h"
+
+namespace zg {
+
+// =================================================================================================
+// device helpers
+// =================================================================================================
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr uint64_t kStAggregate = 1ull << 62; // tile total published
+constexpr uint64_t kStPrefix = 2ull << 62;    // inclusive prefix published
+constexpr uint32_t kSpinLimit = 1u << 22;     // bounded wait: polls before giving up with ZG_FLAG_INTERNAL
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__device__ __forceinline__ void st_store(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint64_t st_load(uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Single-pass chained scan across workgroups: tile `tile` (tickets are handed out in start order, so
+// every predecessor is already running) publishes its total, then wave 0 walks back over the
+// predecessors' status words, 64 at a time, until it meets a published inclusive prefix.  A status word
+// carries state and value together, so one relaxed 64-bit access is enough.  The wait is bounded.
+__device__ uint32_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, uint32_t total, uint32_t *flags, int lane)
+{
+    if (lane == 0) st_store(&status[tile], (tile == 0 ? kStPrefix : kStAggregate) | total);
+    uint32_t excl = 0;
+    if (tile > 0) {
+        int64_t base = (int64_t)tile - 1;
+        uint32_t spins = 0;
+        for (;;) {
+            const int64_t idx = base - lane;
+            uint64_t st;
+            for (;;) {
+                st = idx >= 0 ? st_load(&status[idx]) : kStPrefix;
+                const bool invalid = (st >> 62) == 0;
+                if (!__any(invalid)) break;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) atomicOr(flags, ZG_FLAG_INTERNAL);
+                    if (invalid) st = kStAggregate;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            const unsigned long long pm = __ballot((st >> 62) == 2);
+            const uint32_t val = (uint32_t)st;
+            if (pm) {
+                const int first = __ffsll((long long)pm) - 1;
+                excl += wave_sum(lane <= first ? val : 0u);
+                break;
+            }
+            excl += wave_sum(val);
+            base -= 64;
+        }
+        if (lane == 0) st_store(&status[tile], kStPrefix | (uint64_t)(excl + total));
+    }
+    return excl;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11) for counter (node, slot, hop, 0) and the 64-bit step key;
+// returns the first two output words as one 64-bit draw.
+__device__ __forceinline__ uint64_t philox_draw(uint32_t key_lo, uint32_t key_hi, uint32_t hop, uint32_t node, uint32_t slot)
+{
+    uint32_t c0 = node, c1 = slot, c2 = hop, c3 = 0u;
+    uint32_t k0 = key_lo, k1 = key_hi;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        c0 = h1 ^ c1 ^ k0;
+        c1 = l1;
+        c2 = h0 ^ c3 ^ k1;
+        c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return (uint64_t)c0 | ((uint64_t)c1 << 32);
+}
+
+// =================================================================================================
+// kernels
+// =================================================================================================
+struct IngestArgs {
+    Drmb *drmb;
+    const int32_t *seeds;
+    int32_t *S;
+    int32_t *local_id;
+    uint64_t *status;
+    uint64_t status_words;
+    uint32_t batch;
+    uint32_t num_nodes;
+    uint32_t key_lo, key_hi;
+};
+
+// Step entry: seeds -> D_0 (caller's order) and the id map, step key and counters -> metadata buffer,
+// scan state cleared.  Out-of-range seeds are replaced by -1 (a vertex with no neighbors).
+__global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
+{
+    const uint32_t gtid = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t gsize = gridDim.x * kBlock;
+    if (gtid == 0) {
+        Drmb *d = a.drmb;
+        d->n[0] = a.batch;
+        d->n_exact[0] = a.batch;
+        d->key_lo = a.key_lo;
+        d->key_hi = a.key_hi;
+        d->step_flags = 0;
+        for (int i = 0; i < 2 * ZG_MAX_HOPS; ++i) d->ticket[i] = 0;
+    }
+    for (uint64_t w = gtid; w < a.status_words; w += gsize) a.status[w] = 0;
+    if (gtid < a.batch) {
+        int32_t v = a.seeds[gtid];
+        if ((uint32_t)v >= a.num_nodes) {
+            atomicOr(&a.drmb->flags, ZG_FLAG_SEED_RANGE);
+            atomicOr(&a.drmb->step_flags, ZG_FLAG_SEED_RANGE);
+            v = -1;
+        } else {
+            const int32_t old = atomicCAS(&a.local_id[v], -1, (int32_t)gtid);
+            if (old != -1) {
+                atomicOr(&a.drmb->flags, ZG_FLAG_SEED_DUP);
+                atomicOr(&a.drmb->step_flags, ZG_FLAG_SEED_DUP);
+            }
+        }
+        a.S[gtid] = v;
+    }
+}
+
+struct SampleArgs {
+    const void *offsets;
+    const int32_t *indices;
+    Drmb *drmb;
+    const int32_t *S;
+    int32_t *row_ptr;
+    int32_t *nbr;
+    const int32_t *local_id;
+    uint32_t *bitmap;
+    uint64_t *status;
+    uint32_t num_nodes;
+    int32_t hop;
+    int32_t fanout;
+    int32_t group_log2; // lanes per frontier vertex = 2^group_log2 >= fanout
+    int32_t replace;
+};
+
+// Hop h, steps "row lengths", "offsets scan" and "sample" in one pass.  A workgroup owns a tile of 256
+// frontier vertices: thread i computes k_i = min(F, deg) (2 offset loads), the tile is scanned in LDS and
+// chained to its predecessors, row_ptr is written; then each group of 2^group_log2 lanes takes one
+// vertex at a time, one lane per slot: whole row if deg <= F, else Floyd's subset algorithm with one
+// Philox draw per slot, the "already chosen" test resolved slot by slot with wave ballots.  Sampled ids
+// not yet in the id map are marked in the hop's bitmap.
+template <typename OffT>
+__global__ __launch_bounds__(kBlock) void k_sample_hop(SampleArgs a)
+{
+    __shared__ uint32_t s_tile, s_base;
+    __shared__ uint32_t s_wsum[4];
+    __shared__ int32_t s_v[kSampleTile];
+    __shared__ uint32_t s_deg[kSampleTile], s_k[kSampleTile], s_rp[kSampleTile];
+    __shared__ unsigned long long s_off[kSampleTile];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Drmb *d = a.drmb;
+    if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop], 1u);
+    __syncthreads();
+    const uint32_t tile = s_tile;
+    const uint32_t n = d->n[a.hop];
+    const uint32_t ntiles = (n + kSampleTile - 1) / kSampleTile;
+    if (n == 0 && tile == 0 && tid == 0) {
+        a.row_ptr[0] = 0;
+        d->E[a.hop] = 0;
+    }
+    if (tile >= ntiles) return;
+
+    const OffT *off = (const OffT *)a.offsets;
+    const uint32_t F = (uint32_t)a.fanout;
+    const uint32_t i = tile * kSampleTile + tid;
+    int32_t v = -1;
+    uint32_t deg = 0;
+    unsigned long long o = 0;
+    if (i < n) {
+        v = a.S[i];
+        if (v >= 0) {
+            const OffT o0 = off[v], o1 = off[v + 1];
+            o = (unsigned long long)o0;
+            deg = (uint32_t)(o1 - o0);
+        }
+    }
+    const uint32_t k = a.replace ? (deg > 0 ? F : 0u) : (deg < F ? deg : F);
+    const uint32_t incl = wave_incl_scan(k, lane);
+    if (lane == 63) s_wsum[wave] = incl;
+    s_v[tid] = v;
+    s_deg[tid] = deg;
+    s_k[tid] = k;
+    s_off[tid] = o;
+    __syncthreads();
+    uint32_t wbase = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) wbase += s_wsum[w];
+        total += s_wsum[w];
+    }
+    if (wave == 0) {
+        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
+        if (lane == 0) s_base = e;
+    }
+    __syncthreads();
+    const uint32_t base = s_base;
+    const uint32_t rp = base + wbase + incl - k;
+    s_rp[tid] = rp;
+    if (i < n) a.row_ptr[i] = (int32_t)rp;
+    if (tile == ntiles - 1 && tid == 0) {
+        a.row_ptr[n] = (int32_t)(base + total);
+        d->E[a.hop] = base + total;
+    }
+    __syncthreads();
+
+    // ---- sampling: one group of G lanes per vertex, one lane per slot
+    const int glog = a.group_log2;
+    const int G = 1 << glog;
+    const int gl = lane & (G - 1);
+    const int gbase = lane & ~(G - 1);
+    const unsigned long long gmask = G == 64 ? ~0ull : ((1ull << G) - 1ull);
+    const int ngroups = kBlock >> glog;
+    const int grp = (wave << (6 - glog)) + (lane >> glog);
+    const uint32_t nvalid = n - tile * kSampleTile < (uint32_t)kSampleTile ? n - tile * kSampleTile : (uint32_t)kSampleTile;
+    const uint32_t key_lo = d->key_lo, key_hi = d->key_hi;
+
+    for (int t = grp; t < kSampleTile; t += ngroups) { // same trip count for every group
+        const bool act = (uint32_t)t < nvalid;
+        const int32_t tv = s_v[t];
+        const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
+        const unsigned long long toff = s_off[t];
+        const bool slot = act && (uint32_t)gl < tk;
+        uint32_t pos = (uint32_t)gl;
+        if (a.replace) {
+            if (slot) pos = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
+        } else {
+            const bool floyd = slot && tdeg > F;
+            uint32_t cand = (uint32_t)gl;
+            if (floyd)
+                cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
+                                            (uint64_t)(tdeg - F + (uint32_t)gl) + 1ull);
+            pos = cand;
+            if (__any(floyd)) {
+                // slot jj takes its candidate unless an earlier slot already holds it, then it takes deg-F+jj
+                for (uint32_t jj = 1; jj < F; ++jj) {
+                    const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
+                    const bool hit = (uint32_t)gl < jj && pos == cj;
+                    const unsigned long long m = __ballot(hit);
+                    const bool taken = ((m >> gbase) & gmask) != 0ull;
+                    if ((uint32_t)gl == jj) pos = taken ? (tdeg - F + jj) : cj;
+                }
+            }
+        }
+        if (slot) {
+            const int32_t g = a.indices[toff + pos];
+            a.nbr[trp + (uint32_t)gl] = g;
+            if ((uint32_t)g < a.num_nodes && a.local_id[g] < 0) {
+                const uint32_t w = (uint32_t)g >> 5, b = 1u << (g & 31);
+                if (!(a.bitmap[w] & b)) atomicOr(&a.bitmap[w], b);
+            }
+        }
+    }
+}
+
+struct CompactArgs {
+    Drmb *drmb;
+    uint32_t *bitmap;
+    int32_t *S;
+    int32_t *local_id;
+    uint64_t *status;
+    uint32_t cap_next;
+    int32_t hop;
+};
+
+// Hop h, "compact / rank": the hop's bitmap of new vertices is scanned in one chained pass over
+// |V|/32 words; the rank of a set bit is n_h + (set bits before it), so the new vertices land behind
+// D_h in ascending global id and get their local id at once.  Consumed words are cleared for the next
+// hop.  Entries beyond the cap are dropped (never written) and the hop's overflow bit is raised.
+__global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
+{
+    __shared__ uint32_t s_tile, s_base;
+    __shared__ uint32_t s_wsum[4][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Drmb *d = a.drmb;
+    if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
+    __syncthreads();
+    const uint32_t tile = s_tile;
+    uint4 *bm = reinterpret_cast<uint4 *>(a.bitmap) + (size_t)tile * (kCompactTileWords / 4);
+    uint4 w[4];
+    uint32_t cnt[4], incl[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        w[s] = bm[s * kBlock + tid];
+        cnt[s] = __popc(w[s].x) + __popc(w[s].y) + __popc(w[s].z) + __popc(w[s].w);
+        incl[s] = wave_incl_scan(cnt[s], lane);
+        if (lane == 63) s_wsum[s][wave] = incl[s];
+    }
+    __syncthreads();
+    uint32_t total = 0, my_off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        uint32_t wb = 0, st = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (q < wave) wb += s_wsum[s][q];
+            st += s_wsum[s][q];
+        }
+        my_off[s] = total + wb + incl[s] - cnt[s];
+        total += st;
+    }
+    if (wave == 0) {
+        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
+        if (lane == 0) s_base = e;
+    }
+    __syncthreads();
+    const uint32_t n_h = d->n[a.hop];
+    const uint32_t base = n_h + s_base;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (cnt[s] == 0) continue;
+        uint32_t r = base + my_off[s];
+        const uint32_t word0 = tile * kCompactTileWords + (uint32_t)(s * kBlock + tid) * 4u;
+        const uint32_t ws[4] = {w[s].x, w[s].y, w[s].z, w[s].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t bits = ws[c];
+            while (bits) {
+                const int b = __ffs((int)bits) - 1;
+                bits &= bits - 1;
+                const int32_t gid = (int32_t)(((word0 + c) << 5) + b);
+                if (r < a.cap_next) {
+                    a.S[r] = gid;
+                    a.local_id[gid] = (int32_t)r;
+                }
+                ++r;
+            }
+        }
+        bm[s * kBlock + tid] = make_uint4(0, 0, 0, 0);
+    }
+    if (tile == gridDim.x - 1 && tid == 0) {
+        const uint32_t exact = base + total;
+        d->n_exact[a.hop + 1] = exact;
+        d->n[a.hop + 1] = exact < a.cap_next ? exact : a.cap_next;
+        if (exact > a.cap_next) {
+            atomicOr(&d->flags, ZG_FLAG_HOP_OVERFLOW(a.hop));
+            atomicOr(&d->step_flags, ZG_FLAG_HOP_OVERFLOW(a.hop));
+        }
+    }
+}
+
+struct RelabelArgs {
+    const Drmb *drmb;
+    const int32_t *nbr;
+    const int32_t *local_id;
+    int32_t *col;
+    uint32_t num_nodes;
+    int32_t hop;
+};
+
+// Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
+__global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a)
+{
+    const uint32_t E = a.drmb->E[a.hop];
+    const uint32_t e0 = blockIdx.x * kRelabelPerBlock;
+    if (e0 >= E) return;
+#pragma unroll
+    for (int u = 0; u < kRelabelPerBlock / kBlock; ++u) {
+        const uint32_t e = e0 + u * kBlock + threadIdx.x;
+        if (e < E) {
+            const int32_t g = a.nbr[e];
+            a.col[e] = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
+        }
+    }
+}
+
+struct FinishArgs {
+    Drmb *drmb;
+    const int32_t *S;
+    int32_t *local_id;
+    uint32_t *log;
+    int32_t num_hops;
+};
+
+// End of step: the id map entries of this step's vertices go back to "absent" (the map over |V| is
+// never cleared as a whole), the step is appended to the device-side log, the step counter advances.
+__global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a)
+{
+    const uint32_t n = a.drmb->n[a.num_hops];
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) {
+        const int32_t g = a.S[i];
+        if (g >= 0) a.local_id[g] = -1;
+    }
+    if (i == 0) {
+        Drmb *d = a.drmb;
+        const uint32_t epoch = d->epoch;
+        uint32_t *rec = a.log + (size_t)(epoch % kLogCapacity) * ZG_LOG_STRIDE;
+        int p = 0;
+        rec[p++] = epoch;
+        rec[p++] = d->step_flags;
+        for (int h = 0; h <= a.num_hops; ++h) rec[p++] = d->n[h];
+        for (int h = 0; h < a.num_hops; ++h) rec[p++] = d->E[h];
+        for (int h = 1; h <= a.num_hops; ++h) rec[p++] = d->n_exact[h];
+        d->epoch = epoch + 1;
+    }
+}
+
+struct RowArgs {
+    const float *src;      // gather: feature table; aggregate: input rows
+    float *dst;
+    const int32_t *S;      // gather: global ids
+    const int32_t *row_ptr; // aggregate
+    const int32_t *col;     // aggregate
+    const uint32_t *n_rows; // device address of the row count
+    const uint32_t *n_cols; // aggregate: device address of the number of valid input rows
+    int64_t ld_src, ld_dst;
+    uint64_t inv;
+    uint32_t dimv;
+    uint32_t rows;
+    uint32_t max_fanout;
+};
+
+template <int VEC> struct VecOf;
+template <> struct VecOf<4> {
+    typedef v4f type;
+    static __device__ __forceinline__ v4f zero() { return (v4f){0.0f, 0.0f, 0.0f, 0.0f}; }
+};
+template <> struct VecOf<1> {
+    typedef float type;
+    static __device__ __forceinline__ float zero() { return 0.0f; }
+};
+
+// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the
+// rows as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave
+// width still fill every lane, four loads in flight per lane before the stores.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_gather(RowArgs a)
+{
+    typedef typename VecOf<VEC>::type T;
+    __shared__ int32_t s_id[kBlock];
+    const uint32_t n = *a.n_rows;
+    const uint32_t row0 = blockIdx.x * a.rows;
+    if (row0 >= n) return;
+    const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
+    if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
+    __syncthreads();
+    const uint32_t total = rows * a.dimv;
+    for (uint32_t e0 = threadIdx.x; e0 < total; e0 += 4 * kBlock) {
+        T val[4];
+        uint32_t r[4], c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = e0 + u * kBlock;
+            if (e < total) {
+                r[u] = (uint32_t)(((uint64_t)e * a.inv) >> 32);
+                c[u] = e - r[u] * a.dimv;
+                const int32_t g = s_id[r[u]];
+                val[u] = g >= 0 ? *reinterpret_cast<const T *>(a.src + (int64_t)g * a.ld_src + (int64_t)c[u] * VEC) : VecOf<VEC>::zero();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = e0 + u * kBlock;
+            if (e < total) *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r[u]) * a.ld_dst + (int64_t)c[u] * VEC) = val[u];
+        }
+    }
+}
+
+// "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:].  A workgroup owns `rows`
+// output rows; their row_ptr slice and column ids are staged in LDS, then each lane owns one
+// (row, 16-byte column piece) pair at a time and accumulates over the row's edges in fp32.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a)
+{
+    typedef typename VecOf<VEC>::type T;
+    extern __shared__ int32_t s_mem[];
+    int32_t *s_rp = s_mem;               // [rows+1]
+    int32_t *s_col = s_mem + a.rows + 1; // [rows * max_fanout]
+    const uint32_t n = *a.n_rows;
+    const uint32_t n_in = *a.n_cols;
+    const uint32_t row0 = blockIdx.x * a.rows;
+    if (row0 >= n) return;
+    const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
+    for (uint32_t t = threadIdx.x; t <= rows; t += kBlock) s_rp[t] = a.row_ptr[row0 + t];
+    __syncthreads();
+    const int32_t e_begin = s_rp[0];
+    uint32_t e_count = (uint32_t)(s_rp[rows] - e_begin);
+    if (e_count > a.rows * a.max_fanout) e_count = a.rows * a.max_fanout;
+    for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) s_col[t] = a.col[e_begin + t];
+    __syncthreads();
+    const uint32_t total = rows * a.dimv;
+    for (uint32_t e = threadIdx.x; e < total; e += kBlock) {
+        const uint32_t r = (uint32_t)(((uint64_t)e * a.inv) >> 32);
+        const uint32_t c = e - r * a.dimv;
+        const uint32_t b = (uint32_t)(s_rp[r] - e_begin);
+        uint32_t k = (uint32_t)(s_rp[r + 1] - s_rp[r]);
+        if (b + k > e_count) k = b < e_count ? e_count - b : 0;
+        T acc = VecOf<VEC>::zero();
+#pragma unroll 4
+        for (uint32_t j = 0; j < k; ++j) {
+            const uint32_t cj = (uint32_t)s_col[b + j];
+            if (cj < n_in) acc += *reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
+        }
+        const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
+        *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
+    }
+}
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// graph check: indices in range and rows strictly ascending
+template <typename OffT>
+__global__ void k_validate(const OffT *off, const int32_t *idx, int64_t num_nodes, uint32_t *bad)
+{
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < num_nodes; v += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = (int64_t)off[v], e = (int64_t)off[v + 1];
+        int32_t prev = -1;
+        for (int64_t p = b; p < e; ++p) {
+            const int32_t g = idx[p];
+            if (g < 0 || (int64_t)g >= num_nodes) atomicOr(bad, 1u);
+            if (g <= prev) atomicOr(bad, 2u);
+            prev = g;
+        }
+    }
+}
+
+#define ZG_HIP(call)                                                                                         \
+    do {                                                                                                     \
+        hipError_t e_ = (call);                                                                              \
+        if (e_ != hipSuccess) return fail(ZG_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));       \
+    } while (0)
+
+int validate_graph_device(const zg_graph_t *g)
+{
+    uint32_t *d_bad = nullptr;
+    ZG_HIP(hipMalloc(&d_bad, 4));
+    hipError_t e = hipMemset(d_bad, 0, 4);
+    if (e == hipSuccess) {
+        const int grid = (int)std::min<int64_t>(65535, (g->num_nodes + 255) / 256);
+        if (g->offsets_dtype == ZG_I64)
+            k_validate<int64_t><<<grid, 256>>>((const int64_t *)g->d_offsets, g->d_indices, g->num_nodes, d_bad);
+        else
+            k_validate<int32_t><<<grid, 256>>>((const int32_t *)g->d_offsets, g->d_indices, g->num_nodes, d_bad);
+        e = hipGetLastError();
+    }
+    uint32_t bad = 0;
+    if (e == hipSuccess) e = hipMemcpy(&bad, d_bad, 4, hipMemcpyDeviceToHost);
+    (void)hipFree(d_bad);
+    if (e != hipSuccess) return fail(ZG_EHIP, std::string("graph validation: ") + hipGetErrorString(e));
+    if (bad & 1u) return fail(ZG_EINVAL, "graph validation: a neighbor id is out of range");
+    if (bad & 2u) return fail(ZG_EINVAL, "graph validation: a row is not strictly ascending");
+    return ZG_OK;
+}
+
+} // namespace zg
+
+// =================================================================================================
+// plan
+// =================================================================================================
+using namespace zg;
+
+struct zg_plan_s {
+    const zg_graph_t *graph = nullptr;
+    Layout lay;
+    char *ws = nullptr;
+    uint32_t flags = 0;
+    int32_t batch = 0;
+    int device = -1;
+    const float *d_feat = nullptr;
+    int64_t ld_feat = 0;
+    hipStream_t capture_stream = nullptr;
+    hipGraph_t graph_obj = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+
+    Drmb *drmb() const { return reinterpret_cast<Drmb *>(ws + lay.off_drmb); }
+    uint32_t *log() const { return reinterpret_cast<uint32_t *>(ws + lay.off_log); }
+    int32_t *S() const { return reinterpret_cast<int32_t *>(ws + lay.off_S); }
+    int32_t *row_ptr(int h) const { return reinterpret_cast<int32_t *>(ws + lay.off_row_ptr[h]); }
+    int32_t *nbr(int h) const { return reinterpret_cast<int32_t *>(ws + lay.off_nbr[h]); }
+    int32_t *col(int h) const { return reinterpret_cast<int32_t *>(ws + lay.off_col[h]); }
+    float *X() const { return lay.feat_dim > 0 ? reinterpret_cast<float *>(ws + lay.off_X) : nullptr; }
+    float *agg() const { return lay.feat_dim > 0 ? reinterpret_cast<float *>(ws + lay.off_agg) : nullptr; }
+    int32_t *local_id() const { return reinterpret_cast<int32_t *>(ws + lay.off_local_id); }
+    uint32_t *bitmap() const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap); }
+    uint64_t *status() const { return reinterpret_cast<uint64_t *>(ws + lay.off_status); }
+    uint64_t *status_sample(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_sample[h]); }
+    uint64_t *status_compact(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_compact[h]); }
+};
+
+namespace {
+
+int group_log2_for(int fanout)
+{
+    int g = 0;
+    while ((1 << g) < fanout) ++g;
+    return g;
+}
+
+bool aligned16(const void *p, int64_t ld) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 4) == 0; }
+
+int launch_gather(const zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, hipStream_t st)
+{
+    const int H = p->lay.num_hops;
+    const bool al = aligned16(d_feat, ld) && aligned16(d_out, ld_out);
+    const RowTiling t = gather_tiling(dim, al);
+    RowArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.src = d_feat;
+    a.dst = d_out;
+    a.S = p->S();
+    a.n_rows = &p->drmb()->n[H];
+    a.ld_src = ld;
+    a.ld_dst = ld_out;
+    a.inv = t.inv;
+    a.dimv = t.dimv;
+    a.rows = t.rows;
+    const unsigned grid = (unsigned)((p->lay.node_cap[H] + t.rows - 1) / t.rows);
+    if (t.vec == 4)
+        hipLaunchKernelGGL(k_gather<4>, dim3(grid), dim3(kBlock), 0, st, a);
+    else
+        hipLaunchKernelGGL(k_gather<1>, dim3(grid), dim3(kBlock), 0, st, a);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
+}
+
+int launch_aggregate(const zg_plan_t *p, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
+                     hipStream_t st)
+{
+    const bool al = aligned16(d_in, ld_in) && aligned16(d_out, ld_out);
+    const RowTiling t = aggregate_tiling(dim, al);
+    RowArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.src = d_in;
+    a.dst = d_out;
+    a.row_ptr = p->row_ptr(hop);
+    a.col = p->col(hop);
+    a.n_rows = &p->drmb()->n[hop];
+    a.n_cols = &p->drmb()->n[hop + 1];
+    a.ld_src = ld_in;
+    a.ld_dst = ld_out;
+    a.inv = t.inv;
+    a.dimv = t.dimv;
+    a.rows = t.rows;
+    a.max_fanout = (uint32_t)p->lay.fanout[hop];
+    const unsigned grid = (unsigned)((p->lay.node_cap[hop] + t.rows - 1) / t.rows);
+    const size_t lds = ((size_t)t.rows + 1 + (size_t)t.rows * a.max_fanout) * 4;
+    if (t.vec == 4)
+        hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, a);
+    else
+        hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, a);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
+}
+
+int launch_ingest(const zg_plan_t *p, const int32_t *d_seeds, uint64_t key, hipStream_t st)
+{
+    IngestArgs a;
+    a.drmb = p->drmb();
+    a.seeds = d_seeds;
+    a.S = p->S();
+    a.local_id = p->local_id();
+    a.status = p->status();
+    a.status_words = p->lay.status_words;
+    a.batch = (uint32_t)p->batch;
+    a.num_nodes = (uint32_t)p->graph->num_nodes;
+    a.key_lo = (uint32_t)(key & 0xFFFFFFFFull);
+    a.key_hi = (uint32_t)(key >> 32);
+    const uint64_t work = std::max<uint64_t>((uint64_t)p->batch, std::min<uint64_t>(a.status_words, 1u << 16));
+    const unsigned grid = (unsigned)((work + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(k_ingest, dim3(grid), dim3(kBlock), 0, st, a);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
+}
+
+// everything of a step after the ingest, in order, on one stream (captured once, or issued eagerly)
+int enqueue_body(const zg_plan_t *p, hipStream_t st)
+{
+    const Layout &L = p->lay;
+    const zg_graph_t *g = p->graph;
+    const int H = L.num_hops;
+    for (int h = 0; h < H; ++h) {
+        SampleArgs sa;
+        sa.offsets = g->d_offsets;
+        sa.indices = g->d_indices;
+        sa.drmb = p->drmb();
+        sa.S = p->S();
+        sa.row_ptr = p->row_ptr(h);
+        sa.nbr = p->nbr(h);
+        sa.local_id = p->local_id();
+        sa.bitmap = p->bitmap();
+        sa.status = p->status_sample(h);
+        sa.num_nodes = (uint32_t)g->num_nodes;
+        sa.hop = h;
+        sa.fanout = L.fanout[h];
+        sa.group_log2 = group_log2_for(L.fanout[h]);
+        sa.replace = (p->flags & ZG_PLAN_REPLACE) ? 1 : 0;
+        const unsigned gs = (unsigned)L.sample_tiles[h];
+        if (g->offsets_dtype == ZG_I64)
+            hipLaunchKernelGGL(k_sample_hop<int64_t>, dim3(gs), dim3(kBlock), 0, st, sa);
+        else
+            hipLaunchKernelGGL(k_sample_hop<int32_t>, dim3(gs), dim3(kBlock), 0, st, sa);
+        ZG_HIP(hipGetLastError());
+
+        CompactArgs ca;
+        ca.drmb = p->drmb();
+        ca.bitmap = p->bitmap();
+        ca.S = p->S();
+        ca.local_id = p->local_id();
+        ca.status = p->status_compact(h);
+        ca.cap_next = (uint32_t)L.node_cap[h + 1];
+        ca.hop = h;
+        hipLaunchKernelGGL(k_compact_hop, dim3((unsigned)L.compact_tiles), dim3(kBlock), 0, st, ca);
+        ZG_HIP(hipGetLastError());
+
+        RelabelArgs ra;
+        ra.drmb = p->drmb();
+        ra.nbr = p->nbr(h);
+        ra.local_id = p->local_id();
+        ra.col = p->col(h);
+        ra.num_nodes = (uint32_t)g->num_nodes;
+        ra.hop = h;
+        const unsigned gr = (unsigned)((L.edge_cap[h] + kRelabelPerBlock - 1) / kRelabelPerBlock);
+        hipLaunchKernelGGL(k_relabel_hop, dim3(gr), dim3(kBlock), 0, st, ra);
+        ZG_HIP(hipGetLastError());
+    }
+    if (p->d_feat && L.feat_dim > 0) {
+        int rc = launch_gather(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, st);
+        if (rc != ZG_OK) return rc;
+        rc = launch_aggregate(p, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, st);
+        if (rc != ZG_OK) return rc;
+    }
+    FinishArgs fa;
+    fa.drmb = p->drmb();
+    fa.S = p->S();
+    fa.local_id = p->local_id();
+    fa.log = p->log();
+    fa.num_hops = H;
+    hipLaunchKernelGGL(k_finish, dim3((unsigned)((L.node_cap[H] + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, fa);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
+}
+
+void drop_graph(zg_plan_t *p)
+{
+    if (p->graph_exec) (void)hipGraphExecDestroy(p->graph_exec);
+    if (p->graph_obj) (void)hipGraphDestroy(p->graph_obj);
+    p->graph_exec = nullptr;
+    p->graph_obj = nullptr;
+}
+
+int build_graph(zg_plan_t *p)
+{
+    drop_graph(p);
+    if (p->flags & ZG_PLAN_EAGER) return ZG_OK;
+    if (!p->capture_stream) ZG_HIP(hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking));
+    ZG_HIP(hipStreamBeginCapture(p->capture_stream, hipStreamCaptureModeThreadLocal));
+    int rc = enqueue_body(p, p->capture_stream);
+    hipGraph_t gobj = nullptr;
+    hipError_t e = hipStreamEndCapture(p->capture_stream, &gobj);
+    if (rc != ZG_OK) {
+        if (gobj) (void)hipGraphDestroy(gobj);
+        return rc;
+    }
+    if (e != hipSuccess) return fail(ZG_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    p->graph_obj = gobj;
+    ZG_HIP(hipGraphInstantiate(&p->graph_exec, p->graph_obj, nullptr, nullptr, 0));
+    return ZG_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+            const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return fail(ZG_EINVAL, "null handle pointer");
+    *out = nullptr;
+    if (!g || g->stats_only) return fail(ZG_ESTATE, "zg_plan needs a graph handle with device arrays");
+    Layout L;
+    int rc = compute_layout(g, fanouts, num_hops, batch, env, feat_dim, nullptr, &L);
+    if (rc != ZG_OK) return rc;
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
+        return fail(ZG_EINVAL, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < L.total) return fail(ZG_ENOMEM, "workspace smaller than zg_plan_query's workspace_bytes");
+
+    zg_plan_t *p = new (std::nothrow) zg_plan_t();
+    if (!p) return fail(ZG_ENOMEM, "out of host memory");
+    p->graph = g;
+    p->lay = L;
+    p->ws = static_cast<char *>(d_workspace);
+    p->flags = env->flags;
+    p->batch = batch;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto bail = [&](int code) {
+        zg_plan_destroy(p);
+        return code;
+    };
+    if (hipGetDevice(&p->device) != hipSuccess) return bail(fail(ZG_EHIP, "hipGetDevice failed"));
+    if (p->device != g->device) return bail(fail(ZG_ESTATE, "current device differs from the graph's device"));
+
+    // initial state: metadata and log zero, id map all "absent" (-1), bitmap and scan state zero
+    hipError_t e = hipMemsetAsync(p->ws + L.off_drmb, 0, sizeof(Drmb), st);
+    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_log, 0, (size_t)kLogCapacity * ZG_LOG_STRIDE * 4, st);
+    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_local_id, 0xFF, (size_t)g->num_nodes * 4, st);
+    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap, 0, (size_t)L.bitmap_words * 4, st);
+    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return bail(fail(ZG_EHIP, std::string("initialising the workspace: ") + hipGetErrorString(e)));
+
+    rc = build_graph(p);
+    if (rc != ZG_OK) return bail(rc);
+    *out = p;
+    return ZG_OK;
+}
+
+int zg_plan_destroy(zg_plan_t *p)
+{
+    if (!p) return ZG_OK;
+    drop_graph(p);
+    if (p->capture_stream) (void)hipStreamDestroy(p->capture_stream);
+    delete p;
+    return ZG_OK;
+}
+
+int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld)
+{
+    if (!p) return fail(ZG_EINVAL, "null plan");
+    if (p->lay.feat_dim <= 0) return fail(ZG_ESTATE, "plan was made with feat_dim = 0");
+    if (!d_feat || ld < p->lay.feat_dim) return fail(ZG_EINVAL, "null feature table or ld < feat_dim");
+    p->d_feat = d_feat;
+    p->ld_feat = ld;
+    return build_graph(p);
+}
+
+int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
+{
+    if (!p || !o) return fail(ZG_EINVAL, "null argument");
+    std::memset(o, 0, sizeof(*o));
+    const Layout &L = p->lay;
+    o->num_hops = L.num_hops;
+    o->feat_dim = L.feat_dim;
+    o->d_n = p->drmb()->n;
+    o->d_E = p->drmb()->E;
+    o->d_n_exact = p->drmb()->n_exact;
+    o->d_flags = &p->drmb()->flags;
+    o->d_S = p->S();
+    for (int h = 0; h < L.num_hops; ++h) {
+        o->d_row_ptr[h] = p->row_ptr(h);
+        o->d_nbr_gid[h] = p->nbr(h);
+        o->d_col[h] = p->col(h);
+        o->edge_cap[h] = L.edge_cap[h];
+    }
+    for (int h = 0; h <= L.num_hops; ++h) o->node_cap[h] = L.node_cap[h];
+    o->d_X = p->X();
+    o->ldx = L.ldx;
+    o->d_agg = p->agg();
+    o->ld_agg = L.ldx;
+    o->d_log = p->log();
+    o->log_capacity = kLogCapacity;
+    o->d_epoch = &p->drmb()->epoch;
+    return ZG_OK;
+}
+
+int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream)
+{
+    if (!p || !d_seeds) return fail(ZG_EINVAL, "null argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = launch_ingest(p, d_seeds, rng_key, st);
+    if (rc != ZG_OK) return rc;
+    if (p->flags & ZG_PLAN_EAGER) return enqueue_body(p, st);
+    if (!p->graph_exec) return fail(ZG_ESTATE, "plan has no captured graph");
+    ZG_HIP(hipGraphLaunch(p->graph_exec, st));
+    return ZG_OK;
+}
+
+int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, void *stream)
+{
+    if (!p || !d_feat || !d_out) return fail(ZG_EINVAL, "null argument");
+    if (dim < 1 || dim > 32768 || ld < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
+    return launch_gather(p, d_feat, ld, dim, d_out, ld_out, static_cast<hipStream_t>(stream));
+}
+
+int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
+                      void *stream)
+{
+    if (!p || !d_in || !d_out) return fail(ZG_EINVAL, "null argument");
+    if (hop < 0 || hop >= p->lay.num_hops) return fail(ZG_EINVAL, "hop out of range");
+    if (dim < 1 || dim > 32768 || ld_in < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
+    return launch_aggregate(p, hop, d_in, ld_in, dim, d_out, ld_out, static_cast<hipStream_t>(stream));
+}
+
+int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag)
+{
+    if (!p || !d_flag) return fail(ZG_EINVAL, "null argument");
+    *d_flag = &p->drmb()->flags;
+    return ZG_OK;
+}
+
+int zg_overflow_clear(zg_plan_t *p, void *stream)
+{
+    if (!p) return fail(ZG_EINVAL, "null plan");
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), &p->drmb()->flags, 0u, (size_t)1);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,384 @@
+// Host side of libzg: error reporting, graph handles and degree statistics, the envelope model
+// (paper section 4.3, Lemma 1, appendix A) and the fixed buffer layout / launch caps of a plan.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <map>
+
+#include "zg_internal.h"
+
+namespace zg {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string &msg) { g_last_error = msg; }
+
+int fail(int status, const std::string &msg)
+{
+    set_error(msg);
+    return status;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+RowTiling gather_tiling(int32_t dim, bool aligned16)
+{
+    RowTiling t;
+    t.vec = (aligned16 && dim % 4 == 0) ? 4 : 1;
+    t.dimv = (uint32_t)(dim / t.vec);
+    t.inv = ((1ull << 32) + t.dimv - 1) / t.dimv;
+    t.rows = std::max<uint32_t>(1, std::min<uint32_t>(kBlock, 2048u / t.dimv));
+    return t;
+}
+
+RowTiling aggregate_tiling(int32_t dim, bool aligned16)
+{
+    RowTiling t = gather_tiling(dim, aligned16);
+    t.rows = std::max<uint32_t>(1, std::min<uint32_t>(64, 512u / t.dimv));
+    return t;
+}
+
+// ---- envelope ----------------------------------------------------------------------------------
+
+static int64_t sat_mul_add(int64_t n, int64_t f)
+{
+    // n * (1 + f) without overflow for the sizes that occur (n < 2^31, f <= 64)
+    return n * (1 + f);
+}
+
+int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
+                   int32_t feat_dim, zg_plan_info *info, Layout *lay)
+{
+    if (!g || !fanouts || !env) return fail(ZG_EINVAL, "null argument");
+    if (num_hops < 1 || num_hops > ZG_MAX_HOPS) return fail(ZG_EINVAL, "num_hops must be in 1..ZG_MAX_HOPS");
+    if (batch < 1 || batch > g->num_nodes) return fail(ZG_EINVAL, "batch must be in 1..num_nodes");
+    if (feat_dim < 0 || feat_dim > 32768) return fail(ZG_EINVAL, "feat_dim must be in 0..32768");
+    for (int h = 0; h < num_hops; ++h)
+        if (fanouts[h] < 1 || fanouts[h] > ZG_MAX_FANOUT) return fail(ZG_EINVAL, "fanout must be in 1..ZG_MAX_FANOUT");
+    if (env->mode < ZG_ENV_MAX || env->mode > ZG_ENV_EXPLICIT) return fail(ZG_EINVAL, "unknown envelope mode");
+    const bool replace = (env->flags & ZG_PLAN_REPLACE) != 0;
+    const int64_t V = g->num_nodes;
+
+    zg_plan_info pi;
+    std::memset(&pi, 0, sizeof(pi));
+    pi.num_hops = num_hops;
+    pi.feat_dim = feat_dim;
+
+    // worst case (Eq. 1 applied hop by hop, the frontier carried along, capped by |V|)
+    pi.maxsg_nodes[0] = batch;
+    for (int h = 0; h < num_hops; ++h) pi.maxsg_nodes[h + 1] = std::min<int64_t>(V, sat_mul_add(pi.maxsg_nodes[h], fanouts[h]));
+
+    // Lemma 1 statistics (reported in every mode)
+    double mean[ZG_MAX_HOPS + 1] = {}, sigma[ZG_MAX_HOPS + 1] = {};
+    if (!g->degrees.empty()) {
+        int rc = zg_envelope_model(g->degrees.data(), g->counts.data(), (int64_t)g->degrees.size(), fanouts, num_hops, batch,
+                                   replace ? 1 : 0, mean, sigma);
+        if (rc != ZG_OK) return rc;
+    }
+    const double conf = env->confidence > 0 ? env->confidence : 0.9999;
+    const int64_t iters = env->iterations > 0 ? env->iterations : 1000;
+    const double margin = env->margin >= 0 ? env->margin : 0.20;
+    if (!(conf > 0.0 && conf < 1.0)) return fail(ZG_EINVAL, "confidence must be in (0,1)");
+    pi.z = zg_normal_quantile(std::pow(conf, 1.0 / (double)iters));
+    for (int h = 0; h <= num_hops; ++h) {
+        pi.model_mean[h] = mean[h];
+        pi.model_sigma[h] = sigma[h];
+    }
+
+    auto caps_for = [&](int mode, int64_t *node_cap) -> int {
+        node_cap[0] = batch;
+        for (int h = 0; h < num_hops; ++h) {
+            const int64_t worst = std::min<int64_t>(V, sat_mul_add(node_cap[h], fanouts[h]));
+            int64_t want = worst;
+            if (mode == ZG_ENV_MODEL) {
+                if (g->degrees.empty()) return fail(ZG_ESTATE, "graph handle has no degree statistics");
+                const double a = (1.0 + margin) * mean[h + 1];
+                const double b = mean[h + 1] + pi.z * sigma[h + 1];
+                want = (int64_t)std::ceil(std::max(a, b));
+            } else if (mode == ZG_ENV_EXPLICIT) {
+                want = env->node_caps[h + 1];
+                if (want < 1) return fail(ZG_EINVAL, "explicit node cap < 1");
+            }
+            node_cap[h + 1] = std::max<int64_t>(node_cap[h], std::min<int64_t>(worst, want));
+        }
+        return ZG_OK;
+    };
+    int rc = caps_for(env->mode, pi.node_cap);
+    if (rc != ZG_OK) return rc;
+
+    const int64_t ldx = feat_dim > 0 ? (int64_t)align_up((size_t)feat_dim, 4) : 0;
+    auto envelope_bytes_for = [&](const int64_t *node_cap) -> int64_t {
+        size_t b = align_up(sizeof(Drmb), kAlign) + kGuard + align_up((size_t)kLogCapacity * ZG_LOG_STRIDE * 4, kAlign) + kGuard;
+        b += align_up((size_t)node_cap[num_hops] * 4, kAlign) + kGuard;
+        for (int h = 0; h < num_hops; ++h) {
+            b += align_up((size_t)(node_cap[h] + 1) * 4, kAlign) + kGuard;
+            b += 2 * (align_up((size_t)node_cap[h] * fanouts[h] * 4, kAlign) + kGuard);
+        }
+        if (feat_dim > 0) {
+            b += align_up((size_t)node_cap[num_hops] * ldx * 4, kAlign) + kGuard;
+            b += align_up((size_t)node_cap[num_hops - 1] * ldx * 4, kAlign) + kGuard;
+        }
+        return (int64_t)b;
+    };
+
+    Layout L;
+    L.num_hops = num_hops;
+    L.feat_dim = feat_dim;
+    L.ldx = ldx;
+    for (int h = 0; h <= num_hops; ++h) L.node_cap[h] = pi.node_cap[h];
+    for (int h = 0; h < num_hops; ++h) {
+        L.fanout[h] = fanouts[h];
+        L.edge_cap[h] = L.node_cap[h] * fanouts[h];
+        if (L.edge_cap[h] >= (int64_t)1 << 31) return fail(ZG_EINVAL, "edge capacity of a hop reaches 2^31");
+        pi.edge_cap[h] = L.edge_cap[h];
+        L.sample_tiles[h] = (L.node_cap[h] + kSampleTile - 1) / kSampleTile;
+    }
+    L.bitmap_words = (int64_t)align_up((size_t)((V + 31) / 32), kCompactTileWords);
+    L.compact_tiles = L.bitmap_words / kCompactTileWords;
+
+    size_t off = 0;
+    auto place = [&](size_t bytes) {
+        size_t at = off;
+        off += align_up(bytes, kAlign) + kGuard;
+        return at;
+    };
+    L.off_drmb = place(sizeof(Drmb));
+    L.off_log = place((size_t)kLogCapacity * ZG_LOG_STRIDE * 4);
+    L.off_S = place((size_t)L.node_cap[num_hops] * 4);
+    for (int h = 0; h < num_hops; ++h) {
+        L.off_row_ptr[h] = place((size_t)(L.node_cap[h] + 1) * 4);
+        L.off_nbr[h] = place((size_t)L.edge_cap[h] * 4);
+        L.off_col[h] = place((size_t)L.edge_cap[h] * 4);
+    }
+    if (feat_dim > 0) {
+        L.off_X = place((size_t)L.node_cap[num_hops] * ldx * 4);
+        L.off_agg = place((size_t)L.node_cap[num_hops - 1] * ldx * 4);
+    }
+    L.envelope_end = off;
+    L.off_local_id = place((size_t)V * 4);
+    L.off_bitmap = place((size_t)L.bitmap_words * 4);
+    L.status_words = 0;
+    for (int h = 0; h < num_hops; ++h) L.status_words += (size_t)L.sample_tiles[h] + (size_t)L.compact_tiles;
+    L.off_status = place(L.status_words * 8);
+    size_t w = 0;
+    for (int h = 0; h < num_hops; ++h) {
+        L.off_status_sample[h] = L.off_status + w * 8;
+        w += (size_t)L.sample_tiles[h];
+    }
+    for (int h = 0; h < num_hops; ++h) {
+        L.off_status_compact[h] = L.off_status + w * 8;
+        w += (size_t)L.compact_tiles;
+    }
+    L.total = off;
+
+    pi.envelope_bytes = (int64_t)L.envelope_end;
+    pi.scratch_bytes = (int64_t)(L.total - L.envelope_end);
+    pi.workspace_bytes = (int64_t)L.total;
+    pi.maxsg_envelope_bytes = envelope_bytes_for(pi.maxsg_nodes);
+    for (int h = 0; h < num_hops; ++h) {
+        pi.grid_sample[h] = (int32_t)L.sample_tiles[h];
+        pi.grid_relabel[h] = (int32_t)((L.edge_cap[h] + kRelabelPerBlock - 1) / kRelabelPerBlock);
+    }
+    pi.grid_compact = (int32_t)L.compact_tiles;
+    if (feat_dim > 0) {
+        RowTiling tg = gather_tiling(feat_dim, true), ta = aggregate_tiling(feat_dim, true);
+        pi.grid_gather = (int32_t)((L.node_cap[num_hops] + tg.rows - 1) / tg.rows);
+        pi.grid_aggregate = (int32_t)((L.node_cap[num_hops - 1] + ta.rows - 1) / ta.rows);
+    }
+    if (info) *info = pi;
+    if (lay) *lay = L;
+    return ZG_OK;
+}
+
+} // namespace zg
+
+using namespace zg;
+
+extern "C" {
+
+const char *zg_strerror(int status)
+{
+    switch (status) {
+    case ZG_OK: return "ok";
+    case ZG_EINVAL: return "invalid argument";
+    case ZG_ENOMEM: return "workspace too small or out of host memory";
+    case ZG_EHIP: return "HIP runtime error";
+    case ZG_ESTATE: return "operation not valid in this state";
+    default: return "unknown status";
+    }
+}
+
+const char *zg_last_error(void) { return g_last_error.c_str(); }
+
+double zg_normal_quantile(double p)
+{
+    // Phi(x) = erfc(-x / sqrt 2) / 2 is monotone: bisect on the lower tail, where erfc keeps its
+    // relative accuracy; the upper half follows by symmetry.
+    if (!(p > 0.0 && p < 1.0)) return p <= 0.0 ? -std::numeric_limits<double>::infinity() : std::numeric_limits<double>::infinity();
+    if (p > 0.5) return -zg_normal_quantile(1.0 - p);
+    double lo = -40.0, hi = 0.0;
+    for (int it = 0; it < 200; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        const double cdf = 0.5 * std::erfc(-mid / std::sqrt(2.0));
+        if (cdf < p) lo = mid; else hi = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_distinct, const int32_t *fanouts,
+                      int32_t num_hops, int32_t batch, int32_t with_replacement, double *mean, double *sigma)
+{
+    if (!degrees || !counts || !fanouts || !mean || !sigma || n_distinct < 1 || num_hops < 1 || num_hops > ZG_MAX_HOPS)
+        return fail(ZG_EINVAL, "zg_envelope_model: bad argument");
+    double V = 0, sumdeg = 0;
+    for (int64_t k = 0; k < n_distinct; ++k) {
+        if (degrees[k] < 0 || counts[k] < 0) return fail(ZG_EINVAL, "zg_envelope_model: negative degree or count");
+        V += (double)counts[k];
+        sumdeg += (double)counts[k] * (double)degrees[k];
+    }
+    if (V <= 0) return fail(ZG_EINVAL, "zg_envelope_model: empty graph");
+    auto draws_of = [&](int64_t d, int32_t F) -> double {
+        if (with_replacement) return d > 0 ? (double)F : 0.0;
+        return (double)std::min<int64_t>(d, F);
+    };
+    // hit probability of a vertex of degree d after S draws: 1 - (1 - d/sumdeg)^S
+    auto hit = [&](int64_t d, double S) -> double {
+        if (sumdeg <= 0 || d <= 0 || S <= 0) return 0.0;
+        const double pi = (double)d / sumdeg;
+        if (pi >= 1.0) return 1.0;
+        return -std::expm1(S * std::log1p(-pi));
+    };
+    mean[0] = batch;
+    sigma[0] = 0.0;
+    double S = 0.0;
+    for (int h = 0; h < num_hops; ++h) {
+        double draws = 0.0;
+        for (int64_t k = 0; k < n_distinct; ++k) {
+            const double c = (double)counts[k];
+            // seeds: uniform over V; vertices discovered so far: weighted by their hit probability
+            draws += c * draws_of(degrees[k], fanouts[h]) * ((double)batch / V + hit(degrees[k], S));
+        }
+        S += draws;
+        double mu = 0.0, var = 0.0;
+        for (int64_t k = 0; k < n_distinct; ++k) {
+            const double p = hit(degrees[k], S);
+            mu += (double)counts[k] * p;
+            var += (double)counts[k] * p * (1.0 - p);
+        }
+        mean[h + 1] = std::min(V, (double)batch + mu);
+        sigma[h + 1] = std::sqrt(var);
+    }
+    return ZG_OK;
+}
+
+static void histogram_from_degrees(const std::vector<int64_t> &deg, zg_graph_t *g)
+{
+    std::map<int64_t, int64_t> hist;
+    int64_t maxd = 0;
+    for (int64_t d : deg) maxd = std::max(maxd, d);
+    if (maxd < (int64_t)1 << 26) {
+        std::vector<int64_t> dense((size_t)maxd + 1, 0);
+        for (int64_t d : deg) dense[(size_t)d]++;
+        for (int64_t d = 0; d <= maxd; ++d)
+            if (dense[(size_t)d]) { g->degrees.push_back(d); g->counts.push_back(dense[(size_t)d]); }
+        return;
+    }
+    for (int64_t d : deg) hist[d]++;
+    for (auto &kv : hist) { g->degrees.push_back(kv.first); g->counts.push_back(kv.second); }
+}
+
+int zg_graph_create(zg_graph_t **out, int64_t num_nodes, int64_t num_edges, const void *d_offsets, int32_t offsets_dtype,
+                    const int32_t *d_indices, uint32_t flags)
+{
+    if (!out) return fail(ZG_EINVAL, "null handle pointer");
+    *out = nullptr;
+    if (num_nodes < 1 || num_nodes >= ((int64_t)1 << 31)) return fail(ZG_EINVAL, "num_nodes must be in [1, 2^31)");
+    if (num_edges < 0) return fail(ZG_EINVAL, "num_edges < 0");
+    if (!d_offsets || (!d_indices && num_edges > 0)) return fail(ZG_EINVAL, "null device pointer");
+    if (offsets_dtype != ZG_I32 && offsets_dtype != ZG_I64) return fail(ZG_EINVAL, "offsets_dtype must be ZG_I32 or ZG_I64");
+    if (offsets_dtype == ZG_I32 && num_edges >= ((int64_t)1 << 31)) return fail(ZG_EINVAL, "int32 offsets cannot address num_edges");
+
+    zg_graph_t *g = new (std::nothrow) zg_graph_t();
+    if (!g) return fail(ZG_ENOMEM, "out of host memory");
+    g->num_nodes = num_nodes;
+    g->num_edges = num_edges;
+    g->d_offsets = d_offsets;
+    g->offsets_dtype = offsets_dtype;
+    g->d_indices = d_indices;
+    if (hipGetDevice(&g->device) != hipSuccess) { delete g; return fail(ZG_EHIP, "hipGetDevice failed"); }
+
+    // one read-back of the offsets (init time): degree statistics for the envelope model + sanity checks
+    std::vector<int64_t> deg((size_t)num_nodes);
+    {
+        const size_t esz = offsets_dtype == ZG_I64 ? 8 : 4;
+        std::vector<char> host((size_t)(num_nodes + 1) * esz);
+        hipError_t e = hipMemcpy(host.data(), d_offsets, host.size(), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { delete g; return fail(ZG_EHIP, std::string("reading the offsets back: ") + hipGetErrorString(e)); }
+        auto at = [&](int64_t i) -> int64_t {
+            return offsets_dtype == ZG_I64 ? ((const int64_t *)host.data())[i] : (int64_t)((const int32_t *)host.data())[i];
+        };
+        if (at(0) != 0 || at(num_nodes) != num_edges) { delete g; return fail(ZG_EINVAL, "offsets[0] != 0 or offsets[num_nodes] != num_edges"); }
+        for (int64_t v = 0; v < num_nodes; ++v) {
+            const int64_t d = at(v + 1) - at(v);
+            if (d < 0 || d >= ((int64_t)1 << 31)) { delete g; return fail(ZG_EINVAL, "offsets not monotone or a degree reaches 2^31"); }
+            deg[(size_t)v] = d;
+        }
+    }
+    histogram_from_degrees(deg, g);
+    if (flags & ZG_GRAPH_VALIDATE) {
+        int rc = validate_graph_device(g);
+        if (rc != ZG_OK) { delete g; return rc; }
+    }
+    *out = g;
+    return ZG_OK;
+}
+
+int zg_graph_create_stats(zg_graph_t **out, int64_t num_nodes, int64_t num_edges, const int64_t *degrees, const int64_t *counts,
+                          int64_t n_distinct)
+{
+    if (!out) return fail(ZG_EINVAL, "null handle pointer");
+    *out = nullptr;
+    if (num_nodes < 1 || num_nodes >= ((int64_t)1 << 31) || !degrees || !counts || n_distinct < 1)
+        return fail(ZG_EINVAL, "bad argument");
+    int64_t v = 0, e = 0;
+    for (int64_t k = 0; k < n_distinct; ++k) {
+        if (degrees[k] < 0 || counts[k] < 0) return fail(ZG_EINVAL, "negative degree or count");
+        v += counts[k];
+        e += counts[k] * degrees[k];
+    }
+    if (v != num_nodes || e != num_edges) return fail(ZG_EINVAL, "histogram does not add up to num_nodes / num_edges");
+    zg_graph_t *g = new (std::nothrow) zg_graph_t();
+    if (!g) return fail(ZG_ENOMEM, "out of host memory");
+    g->num_nodes = num_nodes;
+    g->num_edges = num_edges;
+    g->stats_only = true;
+    g->degrees.assign(degrees, degrees + n_distinct);
+    g->counts.assign(counts, counts + n_distinct);
+    *out = g;
+    return ZG_OK;
+}
+
+int zg_graph_destroy(zg_graph_t *g)
+{
+    delete g;
+    return ZG_OK;
+}
+
+int zg_graph_degree_histogram(const zg_graph_t *g, int64_t *n_distinct, const int64_t **degrees, const int64_t **counts)
+{
+    if (!g || !n_distinct || !degrees || !counts) return fail(ZG_EINVAL, "null argument");
+    *n_distinct = (int64_t)g->degrees.size();
+    *degrees = g->degrees.data();
+    *counts = g->counts.data();
+    return ZG_OK;
+}
+
+int zg_plan_query(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
+                  int32_t feat_dim, zg_plan_info *out)
+{
+    if (!out) return fail(ZG_EINVAL, "null output");
+    return compute_layout(g, fanouts, num_hops, batch, env, feat_dim, out, nullptr);
+}
+
+} // extern "C"

@@ -1,0 +1,85 @@
+// Internal declarations shared by the host-side planner and the HIP kernels of libzg.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "zg.h"
+
+namespace zg {
+
+constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts of 64)
+constexpr int kSampleTile = 256;        // frontier vertices per sampling workgroup
+constexpr int kCompactTileWords = 4096; // bitmap words per compaction workgroup (4 x uint4 per thread)
+constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup
+constexpr int kLogCapacity = 1024;      // records in the device-side step log
+constexpr size_t kAlign = 256;          // every buffer starts on a 256-byte boundary ...
+constexpr size_t kGuard = 256;          // ... and is followed by at least this many untouched bytes
+
+// Device-resident metadata buffer (paper section 4.1): every size the step produces lives here, at a
+// fixed address, and is only ever read by kernels.
+struct Drmb {
+    uint32_t n[ZG_MAX_HOPS + 1];       // n[h] = |D_h| (clamped to the cap)
+    uint32_t E[ZG_MAX_HOPS];           // sampled edges of hop h
+    uint32_t n_exact[ZG_MAX_HOPS + 1]; // |S_{h-1}| before clamping
+    uint32_t flags;                    // sticky ZG_FLAG_* bits
+    uint32_t step_flags;               // the same bits, for the current step only
+    uint32_t epoch;                    // steps run so far
+    uint32_t key_lo, key_hi;           // step key
+    uint32_t ticket[2 * ZG_MAX_HOPS];  // tile tickets: [2h] sampling, [2h+1] compaction
+};
+
+struct Layout {
+    int32_t num_hops = 0;
+    int32_t feat_dim = 0;
+    int64_t ldx = 0; // row stride of X and agg in elements (feat_dim rounded up to 4)
+    int64_t node_cap[ZG_MAX_HOPS + 1] = {};
+    int64_t edge_cap[ZG_MAX_HOPS] = {};
+    int32_t fanout[ZG_MAX_HOPS] = {};
+    int64_t bitmap_words = 0; // padded to whole compaction tiles
+    int64_t sample_tiles[ZG_MAX_HOPS] = {};
+    int64_t compact_tiles = 0;
+    // byte offsets into the workspace
+    size_t off_drmb = 0, off_log = 0, off_S = 0;
+    size_t off_row_ptr[ZG_MAX_HOPS] = {}, off_nbr[ZG_MAX_HOPS] = {}, off_col[ZG_MAX_HOPS] = {};
+    size_t off_X = 0, off_agg = 0;
+    size_t envelope_end = 0;
+    size_t off_local_id = 0, off_bitmap = 0, off_status = 0;
+    size_t status_words = 0; // uint64 words: sampling tiles of every hop, then compaction tiles of every hop
+    size_t off_status_sample[ZG_MAX_HOPS] = {}, off_status_compact[ZG_MAX_HOPS] = {};
+    size_t total = 0;
+};
+
+void set_error(const std::string &msg);
+int fail(int status, const std::string &msg);
+
+int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
+                   int32_t feat_dim, zg_plan_info *info, Layout *lay);
+
+// launch shapes of the feature kernels for a row of `dim` floats
+struct RowTiling {
+    int vec;            // floats per lane access: 4 when rows are 16-byte aligned, else 1
+    uint32_t dimv;      // dim / vec
+    uint64_t inv;       // ceil(2^32 / dimv): e / dimv == (e * inv) >> 32 for the small e used
+    uint32_t rows;      // rows per workgroup
+};
+RowTiling gather_tiling(int32_t dim, bool aligned16);
+RowTiling aggregate_tiling(int32_t dim, bool aligned16);
+
+// synchronising device-side check of the CSR arrays (indices in range, rows strictly ascending)
+int validate_graph_device(const zg_graph_t *g);
+
+} // namespace zg
+
+struct zg_graph_s {
+    int64_t num_nodes = 0, num_edges = 0;
+    const void *d_offsets = nullptr;
+    int32_t offsets_dtype = ZG_I32;
+    const int32_t *d_indices = nullptr;
+    bool stats_only = false;
+    int device = -1;
+    std::vector<int64_t> degrees, counts; // distinct degree values (ascending) and how many vertices have each
+};

@@ -1,0 +1,355 @@
+"""Thin ctypes binding over libzg.so (the C-ABI of include/zg.h): argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the library's HIP
+kernels.  There is no fallback: if the library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+MAX_HOPS = 8
+MAX_FANOUT = 64
+LOG_STRIDE = 32
+
+OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+I32, I64 = 0, 1
+GRAPH_VALIDATE = 1
+PLAN_EAGER, PLAN_REPLACE = 1, 2
+ENV_MAX, ENV_MODEL, ENV_EXPLICIT = 0, 1, 2
+FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
+
+
+def FLAG_HOP_OVERFLOW(h: int) -> int:
+    return 1 << h
+
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzg.so")
+
+EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_stats", "zg_graph_destroy",
+           "zg_graph_degree_histogram", "zg_normal_quantile", "zg_envelope_model", "zg_plan_query", "zg_plan",
+           "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
+           "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear"]
+
+
+class Envelope(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("flags", C.c_uint32), ("margin", C.c_double), ("confidence", C.c_double),
+                ("iterations", C.c_int64), ("node_caps", C.c_int64 * (MAX_HOPS + 1))]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [("num_hops", C.c_int32), ("feat_dim", C.c_int32),
+                ("node_cap", C.c_int64 * (MAX_HOPS + 1)), ("edge_cap", C.c_int64 * MAX_HOPS),
+                ("maxsg_nodes", C.c_int64 * (MAX_HOPS + 1)),
+                ("model_mean", C.c_double * (MAX_HOPS + 1)), ("model_sigma", C.c_double * (MAX_HOPS + 1)),
+                ("z", C.c_double),
+                ("envelope_bytes", C.c_int64), ("scratch_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("maxsg_envelope_bytes", C.c_int64),
+                ("grid_sample", C.c_int32 * MAX_HOPS), ("grid_compact", C.c_int32),
+                ("grid_relabel", C.c_int32 * MAX_HOPS), ("grid_gather", C.c_int32), ("grid_aggregate", C.c_int32)]
+
+
+class Outputs(C.Structure):
+    _fields_ = [("num_hops", C.c_int32), ("feat_dim", C.c_int32),
+                ("d_n", C.c_void_p), ("d_E", C.c_void_p), ("d_n_exact", C.c_void_p), ("d_flags", C.c_void_p),
+                ("d_S", C.c_void_p),
+                ("d_row_ptr", C.c_void_p * MAX_HOPS), ("d_nbr_gid", C.c_void_p * MAX_HOPS),
+                ("d_col", C.c_void_p * MAX_HOPS),
+                ("node_cap", C.c_int64 * (MAX_HOPS + 1)), ("edge_cap", C.c_int64 * MAX_HOPS),
+                ("d_X", C.c_void_p), ("ldx", C.c_int64), ("d_agg", C.c_void_p), ("ld_agg", C.c_int64),
+                ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library; raises if it has not been built (python -m paper_2605_29346_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it first (__graft_entry__.build()); "
+                               "there is no fallback path")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, i64, u32, u64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_double
+        P = C.POINTER
+        L.zg_strerror.restype = C.c_char_p
+        L.zg_strerror.argtypes = [C.c_int]
+        L.zg_last_error.restype = C.c_char_p
+        L.zg_last_error.argtypes = []
+        L.zg_graph_create.argtypes = [P(vp), i64, i64, vp, i32, vp, u32]
+        L.zg_graph_create_stats.argtypes = [P(vp), i64, i64, P(i64), P(i64), i64]
+        L.zg_graph_destroy.argtypes = [vp]
+        L.zg_graph_degree_histogram.argtypes = [vp, P(i64), P(P(i64)), P(P(i64))]
+        L.zg_normal_quantile.restype = dbl
+        L.zg_normal_quantile.argtypes = [dbl]
+        L.zg_envelope_model.argtypes = [P(i64), P(i64), i64, P(i32), i32, i32, i32, P(dbl), P(dbl)]
+        L.zg_plan_query.argtypes = [vp, P(i32), i32, i32, P(Envelope), i32, P(PlanInfo)]
+        L.zg_plan.argtypes = [P(vp), vp, P(i32), i32, i32, P(Envelope), i32, vp, C.c_size_t, vp]
+        L.zg_plan_destroy.argtypes = [vp]
+        L.zg_plan_bind_features.argtypes = [vp, vp, i64]
+        L.zg_plan_outputs.argtypes = [vp, P(Outputs)]
+        L.zg_step.argtypes = [vp, vp, u64, vp]
+        L.zg_gather.argtypes = [vp, vp, i64, i32, vp, i64, vp]
+        L.zg_aggregate_mean.argtypes = [vp, i32, vp, i64, i32, vp, i64, vp]
+        L.zg_overflow_flag.argtypes = [vp, P(vp)]
+        L.zg_overflow_clear.argtypes = [vp, vp]
+        for name in EXPORTS:
+            if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class ZgError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        L = lib()
+        super().__init__(f"{L.zg_strerror(status).decode()} ({status}): {L.zg_last_error().decode()}")
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise ZgError(status)
+
+
+def normal_quantile(p: float) -> float:
+    return float(lib().zg_normal_quantile(p))
+
+
+def envelope_model(degrees: Sequence[int], counts: Sequence[int], fanouts: Sequence[int], batch: int,
+                   with_replacement: bool = False):
+    """Lemma 1 mean and sigma of n_h for h = 0..H from a degree histogram (host only)."""
+    n = len(degrees)
+    H = len(fanouts)
+    d = (C.c_int64 * n)(*degrees)
+    c = (C.c_int64 * n)(*counts)
+    f = (C.c_int32 * H)(*fanouts)
+    mean = (C.c_double * (MAX_HOPS + 1))()
+    sigma = (C.c_double * (MAX_HOPS + 1))()
+    _check(lib().zg_envelope_model(d, c, n, f, H, batch, int(with_replacement), mean, sigma))
+    return list(mean[: H + 1]), list(sigma[: H + 1])
+
+
+def make_envelope(mode: int = ENV_MAX, *, flags: int = 0, margin: float = -1.0, confidence: float = 0.0,
+                  iterations: int = 0, node_caps: Optional[Sequence[int]] = None) -> Envelope:
+    e = Envelope()
+    e.mode, e.flags, e.margin, e.confidence, e.iterations = mode, flags, margin, confidence, iterations
+    if node_caps is not None:
+        for h, c in enumerate(node_caps):
+            e.node_caps[h] = int(c)
+    return e
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Graph:
+    """CSR graph on the device (torch tensors: int32/int64 offsets, int32 indices), borrowed by the library."""
+
+    def __init__(self, offsets=None, indices=None, *, validate: bool = False, _handle=None, num_nodes=None):
+        import torch
+        self._h = C.c_void_p()
+        if _handle is not None:
+            self._h = _handle
+            self.num_nodes = num_nodes
+            self.offsets = self.indices = None
+            return
+        assert offsets.is_cuda and indices.is_cuda and offsets.is_contiguous() and indices.is_contiguous()
+        assert offsets.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32
+        self.offsets, self.indices = offsets, indices  # keep alive
+        self.num_nodes = offsets.numel() - 1
+        _check(lib().zg_graph_create(C.byref(self._h), self.num_nodes, indices.numel(), offsets.data_ptr(),
+                                     I64 if offsets.dtype == torch.int64 else I32, indices.data_ptr(),
+                                     GRAPH_VALIDATE if validate else 0))
+
+    @classmethod
+    def from_degree_histogram(cls, degrees: Sequence[int], counts: Sequence[int]) -> "Graph":
+        """Statistics-only handle (no device arrays): good for plan_query on a machine without a GPU."""
+        n = len(degrees)
+        d = (C.c_int64 * n)(*degrees)
+        c = (C.c_int64 * n)(*counts)
+        h = C.c_void_p()
+        nn = sum(counts)
+        ne = sum(int(a) * int(b) for a, b in zip(degrees, counts))
+        _check(lib().zg_graph_create_stats(C.byref(h), nn, ne, d, c, n))
+        return cls(_handle=h, num_nodes=nn)
+
+    def degree_histogram(self):
+        n = C.c_int64()
+        d = C.POINTER(C.c_int64)()
+        c = C.POINTER(C.c_int64)()
+        _check(lib().zg_graph_degree_histogram(self._h, C.byref(n), C.byref(d), C.byref(c)))
+        return [d[i] for i in range(n.value)], [c[i] for i in range(n.value)]
+
+    def plan_query(self, fanouts: Sequence[int], batch: int, env: Optional[Envelope] = None, feat_dim: int = 0) -> PlanInfo:
+        env = env or make_envelope()
+        H = len(fanouts)
+        f = (C.c_int32 * H)(*fanouts)
+        info = PlanInfo()
+        _check(lib().zg_plan_query(self._h, f, H, batch, C.byref(env), feat_dim, C.byref(info)))
+        return info
+
+    def close(self):
+        if self._h:
+            lib().zg_graph_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+@dataclass
+class StepResult:
+    """Host copies of one step's outputs (for checks; the hot path never makes them)."""
+    n: List[int]
+    E: List[int]
+    n_exact: List[int]
+    flags: int
+    S: "object"
+    row_ptr: List["object"]
+    nbr_gid: List["object"]
+    col: List["object"]
+    X: Optional["object"]
+    agg: Optional["object"]
+
+
+class Plan:
+    """A provisioned execution envelope + captured step for (graph, fanouts, batch)."""
+
+    def __init__(self, graph: Graph, fanouts: Sequence[int], batch: int, env: Optional[Envelope] = None,
+                 feat_dim: int = 0, stream=None, workspace_slack: int = 0):
+        import torch
+        self.graph = graph
+        self.fanouts = tuple(int(f) for f in fanouts)
+        self.batch = batch
+        self.env = env or make_envelope()
+        self.feat_dim = feat_dim
+        self.info = graph.plan_query(self.fanouts, batch, self.env, feat_dim)
+        self.workspace = torch.empty(self.info.workspace_bytes + workspace_slack, dtype=torch.uint8, device="cuda")
+        assert self.workspace.data_ptr() % 256 == 0
+        H = len(self.fanouts)
+        f = (C.c_int32 * H)(*self.fanouts)
+        self._h = C.c_void_p()
+        _check(lib().zg_plan(C.byref(self._h), graph._h, f, H, batch, C.byref(self.env), feat_dim,
+                             self.workspace.data_ptr(), self.info.workspace_bytes, _stream_ptr(stream)))
+        self.out = Outputs()
+        _check(lib().zg_plan_outputs(self._h, C.byref(self.out)))
+        self.features = None
+
+    @property
+    def num_hops(self) -> int:
+        return len(self.fanouts)
+
+    def bind_features(self, feat) -> None:
+        import torch
+        assert feat.is_cuda and feat.dtype == torch.float32 and feat.dim() == 2 and feat.stride(1) == 1
+        self.features = feat
+        _check(lib().zg_plan_bind_features(self._h, feat.data_ptr(), feat.stride(0)))
+
+    def step(self, seeds, rng_key: int, stream=None) -> None:
+        """Enqueue one mini-batch (seeds: int32 CUDA tensor of `batch` distinct ids); returns at once."""
+        _check(lib().zg_step(self._h, seeds.data_ptr(), C.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), _stream_ptr(stream)))
+
+    def gather(self, feat, out, stream=None) -> None:
+        _check(lib().zg_gather(self._h, feat.data_ptr(), feat.stride(0), feat.shape[1], out.data_ptr(), out.stride(0),
+                               _stream_ptr(stream)))
+
+    def aggregate_mean(self, hop: int, x, out, stream=None) -> None:
+        _check(lib().zg_aggregate_mean(self._h, hop, x.data_ptr(), x.stride(0), x.shape[1], out.data_ptr(),
+                                       out.stride(0), _stream_ptr(stream)))
+
+    def overflow_flag_ptr(self) -> int:
+        p = C.c_void_p()
+        _check(lib().zg_overflow_flag(self._h, C.byref(p)))
+        return p.value
+
+    def overflow_clear(self, stream=None) -> None:
+        _check(lib().zg_overflow_clear(self._h, _stream_ptr(stream)))
+
+    # ---- views into the workspace (no copies) ----
+    def _view(self, ptr: int, count: int, dtype):
+        import torch
+        off = ptr - self.workspace.data_ptr()
+        nbytes = count * torch.empty(0, dtype=dtype).element_size()
+        assert 0 <= off and off + nbytes <= self.workspace.numel()
+        return self.workspace[off: off + nbytes].view(dtype)
+
+    def view_counts(self):
+        import torch
+        H = self.num_hops
+        return (self._view(self.out.d_n, H + 1, torch.int32), self._view(self.out.d_E, H, torch.int32),
+                self._view(self.out.d_n_exact, H + 1, torch.int32), self._view(self.out.d_flags, 1, torch.int32))
+
+    def view_S(self):
+        import torch
+        return self._view(self.out.d_S, self.out.node_cap[self.num_hops], torch.int32)
+
+    def view_block(self, h: int):
+        import torch
+        return (self._view(self.out.d_row_ptr[h], self.out.node_cap[h] + 1, torch.int32),
+                self._view(self.out.d_nbr_gid[h], self.out.edge_cap[h], torch.int32),
+                self._view(self.out.d_col[h], self.out.edge_cap[h], torch.int32))
+
+    def view_X(self):
+        import torch
+        H = self.num_hops
+        return self._view(self.out.d_X, self.out.node_cap[H] * self.out.ldx, torch.float32).view(-1, self.out.ldx)
+
+    def view_agg(self):
+        import torch
+        H = self.num_hops
+        return self._view(self.out.d_agg, self.out.node_cap[H - 1] * self.out.ld_agg, torch.float32).view(-1, self.out.ld_agg)
+
+    def view_log(self):
+        import torch
+        return self._view(self.out.d_log, self.out.log_capacity * LOG_STRIDE, torch.int32).view(-1, LOG_STRIDE)
+
+    def epoch(self) -> int:
+        import torch
+        return int(self._view(self.out.d_epoch, 1, torch.int32).item())
+
+    def read_step(self, with_features: bool = True) -> StepResult:
+        """Synchronise and copy the last step's outputs to the host (numpy)."""
+        import torch
+        torch.cuda.synchronize()
+        H = self.num_hops
+        n_t, E_t, nx_t, fl_t = self.view_counts()
+        n = [int(x) for x in n_t.cpu().tolist()]
+        E = [int(x) for x in E_t.cpu().tolist()]
+        nx = [int(x) for x in nx_t.cpu().tolist()]
+        flags = int(fl_t.cpu().item()) & 0xFFFFFFFF
+        S = self.view_S()[: n[H]].cpu().numpy()
+        rp, nb, col = [], [], []
+        for h in range(H):
+            r, b, c = self.view_block(h)
+            rp.append(r[: n[h] + 1].cpu().numpy())
+            nb.append(b[: E[h]].cpu().numpy())
+            col.append(c[: E[h]].cpu().numpy())
+        X = agg = None
+        if with_features and self.feat_dim > 0 and self.features is not None:
+            X = self.view_X()[: n[H], : self.feat_dim].cpu().numpy()
+            agg = self.view_agg()[: n[H - 1], : self.feat_dim].cpu().numpy()
+        return StepResult(n, E, nx, flags, S, rp, nb, col, X, agg)
+
+    def close(self):
+        if self._h:
+            lib().zg_plan_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,230 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU checker, element by element.
+Sampled ids, relabel maps and block CSR must be bit-exact; gathered rows bit-exact; the fp32 mean
+aggregation within 1e-5 of the double-accumulated reference (relative to max(|ref|, mean |x|))."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_29346_amd import workloads as W
+from paper_2605_29346_amd import zg
+from gpu_util import agg_error, compare_blocks, compare_features, run_and_compare, to_host_graph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    zg.lib()  # must load: there is no fallback
+
+
+def test_tiny_config_full_compare(oracle):
+    cfg = W.CONFIGS["tiny"]
+    g = cfg.build_graph()
+    feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed)
+    seeds = cfg.seed_pool(g).batch_for(0).numpy()
+    plan, res, ref = run_and_compare(oracle, g, feat, seeds, cfg.fanouts, cfg.key_for(0), label="tiny")
+    assert res.n[0] == 64 and res.E[0] <= 320
+    # same step again on the same plan: identical bytes (state left clean, keyed RNG)
+    plan.step(torch.as_tensor(seeds).cuda(), cfg.key_for(0))
+    res2 = plan.read_step()
+    compare_blocks(res2, ref, "tiny/replay")
+    assert np.array_equal(res2.agg.view(np.uint32), res.agg.view(np.uint32))
+    assert plan.epoch() == 2
+
+
+@pytest.mark.parametrize("nodes,draws,batch,fanouts,i64,dim", [
+    (700, 9000, 37, (3,), False, 8),
+    (5000, 200_000, 300, (4, 2), True, 12),       # several sampling tiles (n_1 > 256), ragged tails
+    (5000, 200_000, 1000, (25, 10), True, 20),    # group width 32 and 16
+    (3000, 60_000, 129, (2, 3, 2), True, 4),
+    (3000, 60_000, 257, (7, 1), False, 100),      # fanout 1, 400-byte rows
+    (2000, 400_000, 64, (64, 33), True, 36),      # widest groups, dense graph
+    (40_000, 300_000, 512, (15, 10, 5), True, 32),  # bitmap spans several compaction tiles... of 131072 ids
+    (300_000, 900_000, 2048, (5, 5), True, 16),   # three compaction tiles, sparse graph with many leaves
+])
+def test_random_graphs(oracle, nodes, draws, batch, fanouts, i64, dim):
+    g = W.rmat_graph(nodes, draws, nodes + batch, offsets_dtype=torch.int64 if i64 else torch.int32)
+    feat = W.feature_table(nodes, dim, 5)
+    og = to_host_graph(oracle, g)
+    pool = W.SeedPool(g, batch, 9)
+    plan = None
+    for step in range(3):
+        seeds = pool.batch_for(step).numpy()
+        plan, res, ref = run_and_compare(oracle, g, feat, seeds, fanouts, 7000 + step, plan=plan, og=og,
+                                         label=f"rmat{nodes}/{step}")
+
+
+def test_eager_and_graph_modes_agree(oracle):
+    g = W.rmat_graph(8000, 150_000, 3)
+    feat = W.feature_table(8000, 24, 1)
+    seeds = W.SeedPool(g, 200, 1).batch_for(0).numpy()
+    _, res_graph, ref = run_and_compare(oracle, g, feat, seeds, (6, 4), 99)
+    _, res_eager, _ = run_and_compare(oracle, g, feat, seeds, (6, 4), 99, env=zg.make_envelope(zg.ENV_MAX, flags=zg.PLAN_EAGER))
+    assert np.array_equal(res_graph.agg.view(np.uint32), res_eager.agg.view(np.uint32))
+
+
+def test_with_replacement(oracle):
+    g = W.rmat_graph(6000, 100_000, 4)
+    feat = W.feature_table(6000, 16, 2)
+    seeds = W.SeedPool(g, 150, 2).batch_for(1).numpy()
+    _, res, ref = run_and_compare(oracle, g, feat, seeds, (5, 3), 1234, replace=True, label="replace")
+    deg = np.diff(g.offsets.numpy())[res.S[: res.n[0]]]
+    assert np.array_equal(np.diff(res.row_ptr[0]), np.where(deg > 0, 5, 0))
+
+
+def test_back_to_back_steps_without_sync(oracle):
+    # many steps enqueued with no host sync in between; the device-side log must show each step's true sizes
+    g = W.rmat_graph(20_000, 500_000, 8)
+    feat = W.feature_table(20_000, 32, 3)
+    og = to_host_graph(oracle, g)
+    pool = W.SeedPool(g, 256, 4)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda(), validate=True)
+    plan = zg.Plan(dg, (10, 5), 256, zg.make_envelope(zg.ENV_MAX), feat_dim=32)
+    plan.bind_features(feat.cuda())
+    batches = [pool.batch_for(s).cuda() for s in range(20)]
+    for s, b in enumerate(batches):
+        plan.step(b, 500 + s)
+    torch.cuda.synchronize()
+    log = plan.view_log().cpu().numpy()
+    refs = [og.sample_blocks(batches[s].cpu().numpy(), (10, 5), 500 + s) for s in range(20)]
+    for s in range(20):
+        rec = log[s]
+        assert rec[0] == s and rec[1] == 0
+        assert list(rec[2:5]) == refs[s].n and list(rec[5:7]) == refs[s].E
+    res = plan.read_step()
+    compare_blocks(res, refs[-1], "last of 20")
+    compare_features(oracle, res, refs[-1], feat.numpy(), "last of 20")
+    # the id map went back to "absent" everywhere: the first step replayed gives its own result again
+    plan.step(batches[0], 500)
+    compare_blocks(plan.read_step(), refs[0], "replay of step 0")
+
+
+def test_overflow_is_flagged_clamped_and_leaves_guards_intact(oracle):
+    g = W.rmat_graph(20_000, 500_000, 8)
+    og = to_host_graph(oracle, g)
+    seeds = W.SeedPool(g, 256, 4).batch_for(0).numpy()
+    ref = og.sample_blocks(seeds, (10, 5), 77)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    feat = W.feature_table(20_000, 8, 3).cuda()
+    # hop 1 cap below the true size: overflow at hop 1 only
+    caps = [0, ref.n[1], ref.n[2] - 100]
+    plan = zg.Plan(dg, (10, 5), 256, zg.make_envelope(zg.ENV_EXPLICIT, node_caps=caps), feat_dim=8, workspace_slack=0)
+    plan.bind_features(feat)
+    # a pattern in the guard zone (>= 256 untouched bytes) behind every output buffer
+    out = plan.out
+    base = plan.workspace.data_ptr()
+    H = 2
+    bufs = [(out.d_S, out.node_cap[H] * 4)]
+    for h in range(H):
+        bufs += [(out.d_row_ptr[h], (out.node_cap[h] + 1) * 4), (out.d_nbr_gid[h], out.edge_cap[h] * 4),
+                 (out.d_col[h], out.edge_cap[h] * 4)]
+    bufs += [(out.d_X, out.node_cap[H] * out.ldx * 4), (out.d_agg, out.node_cap[H - 1] * out.ld_agg * 4)]
+    guards = [(ptr - base + nbytes, ptr - base + nbytes + 256) for ptr, nbytes in bufs]
+    for a, b in guards:
+        plan.workspace[a:b] = 0xA5
+    plan.step(torch.as_tensor(seeds).cuda(), 77)
+    torch.cuda.synchronize()
+    n, E, n_exact, flags = [t.cpu().numpy() for t in plan.view_counts()]
+    assert int(flags[0]) == zg.FLAG_HOP_OVERFLOW(1)
+    assert list(n) == [256, ref.n[1], ref.n[2] - 100] and list(n_exact[1:]) == ref.n[1:]
+    for a, b in guards:
+        assert bool((plan.workspace[a:b] == 0xA5).all()), "a kernel wrote past a buffer's capacity"
+    # hop 0 is still exact; hop 1 keeps every vertex below the cap and marks dropped ones with -1
+    S = plan.view_S()[: n[2]].cpu().numpy()
+    assert np.array_equal(S, ref.S[: n[2]])
+    rp1, nb1, col1 = [t.cpu().numpy() for t in plan.view_block(1)]
+    col1 = col1[: E[1]]
+    keep = ref.col[1] < n[2]
+    assert np.array_equal(col1[keep], ref.col[1][keep]) and np.all(col1[~keep] == -1)
+    # the flag is sticky until cleared; the same batch on a worst-case plan gives the full result
+    plan.overflow_clear()
+    torch.cuda.synchronize()
+    assert int(plan.view_counts()[3].cpu()[0]) == 0
+    plan2 = zg.Plan(dg, (10, 5), 256, zg.make_envelope(zg.ENV_MAX), feat_dim=0)
+    plan2.step(torch.as_tensor(seeds).cuda(), 77)
+    compare_blocks(plan2.read_step(), ref, "safe plan")
+    # and the tight plan still works on a later batch that fits
+    small = seeds[:256].copy()
+    plan.step(torch.as_tensor(small).cuda(), 78)
+    torch.cuda.synchronize()
+
+
+def test_bad_seeds_raise_flags_not_faults(oracle):
+    g = W.rmat_graph(5000, 80_000, 6)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    plan = zg.Plan(dg, (4, 4), 8, zg.make_envelope(zg.ENV_MAX))
+    plan.step(torch.tensor([1, 2, 3, 4, 5, 6, 7, 5000], dtype=torch.int32).cuda(), 1)
+    torch.cuda.synchronize()
+    assert int(plan.view_counts()[3].cpu()[0]) & zg.FLAG_SEED_RANGE
+    plan.overflow_clear()
+    plan.step(torch.tensor([1, 2, 3, 4, 5, 6, 7, 3], dtype=torch.int32).cuda(), 1)
+    torch.cuda.synchronize()
+    assert int(plan.view_counts()[3].cpu()[0]) & zg.FLAG_SEED_DUP
+    plan.overflow_clear()
+    # a clean batch afterwards is exact again
+    og = to_host_graph(oracle, g)
+    seeds = np.arange(10, 18, dtype=np.int32)
+    plan.step(torch.as_tensor(seeds).cuda(), 2)
+    compare_blocks(plan.read_step(), og.sample_blocks(seeds, (4, 4), 2), "after bad seeds")
+
+
+@pytest.mark.parametrize("dim,ld", [(1, 1), (3, 5), (7, 7), (30, 32), (600, 600), (1028, 1028), (2100, 2104)])
+def test_standalone_gather_and_aggregate_any_hop(oracle, dim, ld):
+    g = W.rmat_graph(4000, 90_000, 12)
+    og = to_host_graph(oracle, g)
+    seeds = W.SeedPool(g, 100, 6).batch_for(0).numpy()
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    plan = zg.Plan(dg, (5, 4), 100, zg.make_envelope(zg.ENV_MAX))
+    plan.step(torch.as_tensor(seeds).cuda(), 31)
+    res = plan.read_step()
+    ref = og.sample_blocks(seeds, (5, 4), 31)
+    compare_blocks(res, ref)
+    feat = torch.zeros(4000, ld)
+    feat[:, :dim] = W.feature_table(4000, dim, 8)
+    feat_d = feat.cuda()
+    X = torch.full((res.n[2] + 3, ld), -7.0, device="cuda")
+    plan.gather(feat_d[:, :dim], X[:, :dim])
+    torch.cuda.synchronize()
+    Xh = X.cpu().numpy()
+    assert np.array_equal(Xh[: res.n[2], :dim], feat.numpy()[ref.S][:, :dim])
+    assert np.all(Xh[res.n[2]:] == -7.0) and np.all(Xh[:, dim:] == -7.0)
+    for hop in (0, 1):
+        out = torch.full((res.n[hop] + 2, ld), 5.0, device="cuda")
+        plan.aggregate_mean(hop, X[:, :dim], out[:, :dim])
+        torch.cuda.synchronize()
+        Xc = np.ascontiguousarray(Xh[: res.n[hop + 1], :dim])
+        want = oracle.aggregate_mean(ref.row_ptr[hop], ref.col[hop], Xc)
+        got = out.cpu().numpy()
+        assert agg_error(oracle, got[: res.n[hop], :dim], want, ref.row_ptr[hop], ref.col[hop], Xc) <= 1e-5
+        assert np.all(got[res.n[hop]:] == 5.0) and np.all(got[:, dim:] == 5.0)
+
+
+def test_all_ones_and_id_features(oracle):
+    g = W.rmat_graph(9000, 120_000, 2)
+    n = g.num_nodes
+    feat = torch.stack([torch.arange(n, dtype=torch.float32), torch.ones(n), -2.0 * torch.arange(n, dtype=torch.float32),
+                        torch.zeros(n)], 1)
+    seeds = W.SeedPool(g, 300, 6).batch_for(2).numpy()
+    _, res, ref = run_and_compare(oracle, g, feat, seeds, (5, 5), 5)
+    k = np.diff(res.row_ptr[-1])
+    assert np.array_equal(res.X[:, 0].astype(np.int64), res.S)
+    assert np.all(res.agg[k > 0, 1] == 1.0) and np.all(res.agg[k == 0] == 0.0)
+
+
+def test_api_errors():
+    g = W.rmat_graph(1000, 5000, 1)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda(), validate=True)
+    with pytest.raises(zg.ZgError):
+        zg.Plan(dg, (65,), 10)
+    plan = zg.Plan(dg, (3,), 10)
+    with pytest.raises(zg.ZgError) as ei:
+        plan.bind_features(torch.zeros(1000, 4, device="cuda"))
+    assert ei.value.status == zg.ESTATE
+    with pytest.raises(zg.ZgError):
+        plan.aggregate_mean(1, torch.zeros(4, 4, device="cuda"), torch.zeros(4, 4, device="cuda"))
+    bad = g.indices.clone()
+    bad[0] = 5000
+    with pytest.raises(zg.ZgError):
+        zg.Graph(g.offsets.cuda(), bad.cuda(), validate=True)

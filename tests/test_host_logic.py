@@ -1,0 +1,159 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/zg.h declares, and its
+host-side planner (envelope model of Lemma 1 / appendix A, caps, layout) is right."""
+import ctypes
+import math
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2605_29346_amd import zg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "zg.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(zg_[a-z_0-9]+)\s*\(", hdr))
+    assert {"zg_graph_create", "zg_plan", "zg_step", "zg_gather", "zg_aggregate_mean", "zg_overflow_flag"} <= declared
+    L = zg.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in zg.h but not exported"
+    assert declared == set(zg.EXPORTS)
+
+
+def test_struct_sizes_match_header_layout(tmp_path):
+    # compile the header with gcc (it is plain C) and compare sizeof with the ctypes mirrors
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "zg.h"\nint main(void){printf("%zu %zu %zu\\n", '
+                   'sizeof(zg_envelope), sizeof(zg_plan_info), sizeof(zg_outputs));return 0;}\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [ctypes.sizeof(zg.Envelope), ctypes.sizeof(zg.PlanInfo), ctypes.sizeof(zg.Outputs)]
+
+
+def test_normal_quantile_against_scipy_and_appendix_values():
+    from scipy.stats import norm
+    for p in (0.5, 0.9, 0.975, 0.999, 1e-6, 1 - 1e-9):
+        assert abs(zg.normal_quantile(p) - norm.ppf(p)) < 1e-9
+    # z_p^(m) = Phi^-1(p^(1/m)) (appendix A)
+    assert abs(zg.normal_quantile(0.999 ** (1 / 1000)) - 4.753) < 2e-3
+    assert abs(zg.normal_quantile(0.9999 ** (1 / 500)) - 5.069) < 2e-3
+
+
+def test_envelope_model_regular_graph_closed_form():
+    # every vertex has degree d: pi_v = 1/V, p = 1-(1-1/V)^S, mean = B + V p, sigma^2 = V p (1-p)
+    V, d, B, F = 50_000, 12, 256, (5, 3)
+    mean, sigma = zg.envelope_model([d], [V], F, B)
+    S0 = B * min(F[0], d)
+    p0 = 1 - (1 - 1 / V) ** S0
+    assert mean[0] == B and sigma[0] == 0
+    assert abs(mean[1] - (B + V * p0)) < 1e-6 * mean[1]
+    assert abs(sigma[1] - math.sqrt(V * p0 * (1 - p0))) < 1e-6 * sigma[1]
+    S1 = S0 + (B + V * p0) * min(F[1], d)
+    p1 = 1 - (1 - 1 / V) ** S1
+    assert abs(mean[2] - (B + V * p1)) < 1e-6 * mean[2]
+    # sparse regime: sigma^2 ~ mu, CV ~ 1/sqrt(mu)
+    mu = V * p0
+    assert abs(sigma[1] ** 2 / mu - 1) < 0.05
+
+
+def test_envelope_model_against_simulation_of_its_own_assumptions():
+    # Lemma 1's setting: S draws, each hitting vertex v with probability deg(v)/sum(deg); count distinct hits
+    rnd = np.random.RandomState(0)
+    deg = np.concatenate([np.full(4000, 2), np.full(800, 20), np.full(40, 400), np.zeros(500, dtype=int)])
+    vals, cnts = np.unique(deg, return_counts=True)
+    B, F = 64, (4,)
+    mean, sigma = zg.envelope_model(vals.tolist(), cnts.tolist(), F, B, with_replacement=True)
+    S = B * F[0] * (deg > 0).mean()  # seeds uniform over V, F draws when deg > 0
+    pi = deg / deg.sum()
+    sizes, sizes_poisson = [], []
+    for _ in range(600):
+        hits = rnd.choice(len(deg), size=int(round(S)), p=pi)
+        sizes.append(len(np.unique(hits)))
+        hits = rnd.choice(len(deg), size=rnd.poisson(S), p=pi)
+        sizes_poisson.append(len(np.unique(hits)))
+    assert abs((mean[1] - B) - np.mean(sizes)) < 0.02 * np.mean(sizes)
+    # with exactly S draws the indicators are negatively correlated, so sum p(1-p) over-estimates the
+    # spread (the conservative side); with a Poisson number of draws they are independent, as the proof assumes
+    assert np.std(sizes) < 1.05 * sigma[1]
+    assert abs(sigma[1] - np.std(sizes_poisson)) < 0.15 * sigma[1]
+
+
+def _stats_graph():
+    # 10_000 vertices: 9_000 of degree 3, 900 of degree 50, 100 of degree 1000
+    return zg.Graph.from_degree_histogram([3, 50, 1000], [9000, 900, 100])
+
+
+def test_plan_query_max_envelope_is_eq1_hop_by_hop():
+    g = _stats_graph()
+    info = g.plan_query((5, 4, 3), 100, zg.make_envelope(zg.ENV_MAX), feat_dim=16)
+    assert list(info.node_cap[:4]) == [100, 600, 3000, 10_000]  # n(1+F), capped by |V|
+    assert list(info.maxsg_nodes[:4]) == [100, 600, 3000, 10_000]
+    assert list(info.edge_cap[:3]) == [500, 2400, 9000]
+    assert info.envelope_bytes == info.maxsg_envelope_bytes
+    assert info.workspace_bytes == info.envelope_bytes + info.scratch_bytes
+    assert info.scratch_bytes >= 10_000 * 4 + 10_000 // 8
+    assert list(info.grid_sample[:3]) == [1, 3, 12]
+
+
+def test_plan_query_model_envelope_uses_margin_and_z():
+    g = _stats_graph()
+    env = zg.make_envelope(zg.ENV_MODEL, margin=0.2, confidence=0.999, iterations=1000)
+    info = g.plan_query((5, 4), 100, env, feat_dim=8)
+    vals, cnts = g.degree_histogram()
+    mean, sigma = zg.envelope_model(vals, cnts, (5, 4), 100)
+    assert abs(info.z - 4.753) < 2e-3
+    for h in (1, 2):
+        want = math.ceil(max(1.2 * mean[h], mean[h] + info.z * sigma[h]))
+        worst = min(10_000, info.node_cap[h - 1] * (1 + (5, 4)[h - 1]))
+        assert info.node_cap[h] == max(info.node_cap[h - 1], min(worst, want))
+        assert abs(info.model_mean[h] - mean[h]) < 1e-9
+    assert info.envelope_bytes < info.maxsg_envelope_bytes
+    # default margin is 20 %
+    info2 = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MODEL, confidence=0.999, iterations=1000), feat_dim=8)
+    assert list(info2.node_cap[:3]) == list(info.node_cap[:3])
+
+
+def test_plan_query_explicit_and_errors():
+    g = _stats_graph()
+    info = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_EXPLICIT, node_caps=[0, 450, 999_999]))
+    assert list(info.node_cap[:3]) == [100, 450, 2250]  # second cap clamped to 450*(1+4)
+    with pytest.raises(zg.ZgError):
+        g.plan_query((5, 65), 100)
+    with pytest.raises(zg.ZgError):
+        g.plan_query((0,), 100)
+    with pytest.raises(zg.ZgError):
+        g.plan_query((5,), 20_000)
+    with pytest.raises(zg.ZgError):
+        g.plan_query((5,) * 9, 10)
+    with pytest.raises(zg.ZgError) as ei:
+        zg.Graph.from_degree_histogram([3, -1], [5, 5])
+    assert ei.value.status == zg.EINVAL
+
+
+def test_oracle_sizes_stay_inside_max_envelope_and_near_model(oracle):
+    # realised sizes from the checker vs the planner's bounds, on a small R-MAT graph
+    import torch
+    from paper_2605_29346_amd import workloads as W
+    g = W.rmat_graph(20_000, 400_000, 5)
+    off = g.offsets.numpy()
+    deg = np.diff(off)
+    vals, cnts = np.unique(deg, return_counts=True)
+    sg = zg.Graph.from_degree_histogram(vals.tolist(), cnts.tolist())
+    fan, B = (10, 5), 256
+    info = sg.plan_query(fan, B, zg.make_envelope(zg.ENV_MAX))
+    og = oracle.Graph(off, g.indices.numpy())
+    pool = W.SeedPool(g, B, 3)
+    for s in range(5):
+        b = og.sample_blocks(pool.batch_for(s).numpy(), fan, 100 + s)
+        for h in range(3):
+            assert b.n[h] <= info.node_cap[h]
+        for h in range(2):
+            assert b.E[h] <= info.edge_cap[h]
+        assert b.n[2] < info.maxsg_nodes[2]  # shortfall + dedup keep it below the worst case
