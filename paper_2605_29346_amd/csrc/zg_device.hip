@@ -1,6 +1,9 @@
 // HIP kernels (gfx950, wave64) and the plan / step entry points of libzg.
 //
-// One step = ingest, then per hop {sample, compact, relabel}, then gather, aggregate, finish.
+// One step = ingest; per hop h: {sample hop h  +  relabel the edges of hop h-1}, {compact hop h};
+// then {gather + relabel the last hop}, {aggregate + finish}: 2H+3 launches.  Work that only depends on
+// the same predecessor shares a launch (the workgroups of a launch are split by role), because at
+// mini-batch sizes a launch costs about as much as the small kernels themselves.
 // Every kernel is launched with a grid fixed by the plan's capacity envelope, reads the true sizes
 // from the device-resident metadata buffer and lets surplus workgroups return at once (paper
 // sections 4.1-4.3).  Everything after the ingest is one hipGraph (section 4.4).
@@ -118,6 +121,7 @@ struct IngestArgs {
     const int32_t *seeds;
     int32_t *S;
     int32_t *local_id;
+    uint32_t *seen;
     uint64_t *status;
     uint64_t status_words;
     uint32_t batch;
@@ -125,8 +129,9 @@ struct IngestArgs {
     uint32_t key_lo, key_hi;
 };
 
-// Step entry: seeds -> D_0 (caller's order) and the id map, step key and counters -> metadata buffer,
-// scan state cleared.  Out-of-range seeds are replaced by -1 (a vertex with no neighbors).
+// Step entry: seeds -> D_0 (caller's order), their local ids and "seen" bits; step key and counters ->
+// metadata buffer; scan state cleared.  Out-of-range seeds are replaced by -1 (a vertex with no
+// neighbors); a seed whose "seen" bit is already set is a duplicate.
 __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
 {
     const uint32_t gtid = blockIdx.x * kBlock + threadIdx.x;
@@ -148,13 +153,41 @@ __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
             atomicOr(&a.drmb->step_flags, ZG_FLAG_SEED_RANGE);
             v = -1;
         } else {
-            const int32_t old = atomicCAS(&a.local_id[v], -1, (int32_t)gtid);
-            if (old != -1) {
+            const uint32_t bit = 1u << (v & 31);
+            const uint32_t old = atomicOr(&a.seen[(uint32_t)v >> 5], bit);
+            if (old & bit) {
                 atomicOr(&a.drmb->flags, ZG_FLAG_SEED_DUP);
                 atomicOr(&a.drmb->step_flags, ZG_FLAG_SEED_DUP);
             }
+            a.local_id[v] = (int32_t)gtid;
         }
         a.S[gtid] = v;
+    }
+}
+
+struct RelabelArgs {
+    const Drmb *drmb;
+    const int32_t *nbr;
+    const int32_t *local_id;
+    int32_t *col;
+    uint32_t num_nodes;
+    int32_t hop;
+    uint32_t blocks; // workgroups given to this role (0: role absent)
+};
+
+// Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
+// Every sampled id is in S_h, so its map entry was written during this step (by the ingest or a compaction).
+// Works for any workgroup size; a workgroup covers kRelabelPerBlock edges.
+__device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t block)
+{
+    const uint32_t E = a.drmb->E[a.hop];
+    const uint32_t e0 = block * kRelabelPerBlock;
+    if (e0 >= E) return;
+    const uint32_t e1 = e0 + kRelabelPerBlock < E ? e0 + kRelabelPerBlock : E;
+#pragma unroll 4
+    for (uint32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
+        const int32_t g = a.nbr[e];
+        a.col[e] = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
     }
 }
 
@@ -165,65 +198,87 @@ struct SampleArgs {
     const int32_t *S;
     int32_t *row_ptr;
     int32_t *nbr;
-    const int32_t *local_id;
     uint32_t *bitmap;
+    const uint32_t *seen;
     uint64_t *status;
     uint32_t num_nodes;
     int32_t hop;
     int32_t fanout;
-    int32_t group_log2; // lanes per frontier vertex = 2^group_log2 >= fanout
+    int32_t group_log2; // lanes per frontier vertex: 2^group_log2 >= max(4, fanout)
     int32_t replace;
+    uint32_t blocks;    // sampling tiles (the launch's first workgroups)
 };
 
-// Hop h, steps "row lengths", "offsets scan" and "sample" in one pass.  A workgroup owns a tile of 256
-// frontier vertices: thread i computes k_i = min(F, deg) (2 offset loads), the tile is scanned in LDS and
-// chained to its predecessors, row_ptr is written; then each group of 2^group_log2 lanes takes one
-// vertex at a time, one lane per slot: whole row if deg <= F, else Floyd's subset algorithm with one
-// Philox draw per slot, the "already chosen" test resolved slot by slot with wave ballots.  Sampled ids
-// not yet in the id map are marked in the hop's bitmap.
+// Hop h: "row lengths", "offsets scan" and "sample" in one pass, sharing its launch with the edge relabel
+// of hop h-1 (workgroups >= sa.blocks).  A sampling workgroup has 1024 lanes and owns a tile of
+// T = 1024 / G frontier vertices, G = 2^group_log2 lanes per vertex, one lane per sampled slot, so that no
+// lane ever loops: the step is latency-bound at mini-batch sizes and the dependent chain (ticket, frontier
+// id, two offsets, chained scan, neighbor id, bitmap word) is what sets its time.  The first T lanes compute
+// k_i = min(F, deg), the tile is scanned and chained to its predecessors, row_ptr is written.  Then lane
+// (t, j) finds slot j's neighbor position of vertex t: j itself if deg <= F, else Floyd's subset algorithm
+// with one Philox draw per slot.  Floyd's "already chosen" test is sequential over the slots as written;
+// here it is resolved for all slots at once: the set before slot i always contains every earlier candidate,
+// plus deg-F+a for each earlier slot a that collided, so slot i collides iff an earlier slot has the same
+// candidate, or its candidate is deg-F+a for an earlier slot a that collided - an all-pairs compare with
+// independent shuffles and a short fixed-point loop.  The lane then loads the neighbor id and stores it to
+// nbr_gid (consecutive lanes, consecutive addresses).  Dedup starts here: ids already in D_h ("seen" bit,
+// an ordinary cached load) are dropped, the rest go through a hash set in LDS so that each distinct id of
+// the tile reaches the hop's bitmap with at most one device-scope atomic - popular vertices are sampled
+// hundreds of times per hop and same-address atomics serialise at the memory side.
 template <typename OffT>
-__global__ __launch_bounds__(kBlock) void k_sample_hop(SampleArgs a)
+__global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, RelabelArgs prev)
 {
+    if (blockIdx.x >= a.blocks) {
+        relabel_block(prev, blockIdx.x - a.blocks);
+        return;
+    }
     __shared__ uint32_t s_tile, s_base;
     __shared__ uint32_t s_wsum[4];
-    __shared__ int32_t s_v[kSampleTile];
-    __shared__ uint32_t s_deg[kSampleTile], s_k[kSampleTile], s_rp[kSampleTile];
-    __shared__ unsigned long long s_off[kSampleTile];
+    __shared__ int32_t s_v[256];
+    __shared__ uint32_t s_deg[256], s_k[256], s_rp[256];
+    __shared__ unsigned long long s_off[256];
+    __shared__ uint32_t s_set[kSampleHashSlots];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int q = tid; q < kSampleHashSlots; q += kSampleBlock) s_set[q] = 0xFFFFFFFFu;
+    const int glog = a.group_log2;
+    const uint32_t T = (uint32_t)kSampleBlock >> glog; // vertices per tile, 16..256
     Drmb *d = a.drmb;
+    const uint32_t n = d->n[a.hop];
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop], 1u);
     __syncthreads();
     const uint32_t tile = s_tile;
-    const uint32_t n = d->n[a.hop];
-    const uint32_t ntiles = (n + kSampleTile - 1) / kSampleTile;
+    const uint32_t ntiles = (n + T - 1) / T;
     if (n == 0 && tile == 0 && tid == 0) {
         a.row_ptr[0] = 0;
         d->E[a.hop] = 0;
     }
     if (tile >= ntiles) return;
 
-    const OffT *off = (const OffT *)a.offsets;
     const uint32_t F = (uint32_t)a.fanout;
-    const uint32_t i = tile * kSampleTile + tid;
-    int32_t v = -1;
-    uint32_t deg = 0;
-    unsigned long long o = 0;
-    if (i < n) {
-        v = a.S[i];
-        if (v >= 0) {
-            const OffT o0 = off[v], o1 = off[v + 1];
-            o = (unsigned long long)o0;
-            deg = (uint32_t)(o1 - o0);
+    const uint32_t i = tile * T + (uint32_t)tid;
+    uint32_t k = 0, incl = 0;
+    if (wave < 4) { // lanes 0..255 cover the tile's vertices (T <= 256)
+        const OffT *off = (const OffT *)a.offsets;
+        int32_t v = -1;
+        uint32_t deg = 0;
+        unsigned long long o = 0;
+        if ((uint32_t)tid < T && i < n) {
+            v = a.S[i];
+            if (v >= 0) {
+                const OffT o0 = off[v], o1 = off[v + 1];
+                o = (unsigned long long)o0;
+                deg = (uint32_t)(o1 - o0);
+            }
         }
+        k = a.replace ? (deg > 0 ? F : 0u) : (deg < F ? deg : F);
+        incl = wave_incl_scan(k, lane);
+        if (lane == 63) s_wsum[wave] = incl;
+        s_v[tid] = v;
+        s_deg[tid] = deg;
+        s_k[tid] = k;
+        s_off[tid] = o;
     }
-    const uint32_t k = a.replace ? (deg > 0 ? F : 0u) : (deg < F ? deg : F);
-    const uint32_t incl = wave_incl_scan(k, lane);
-    if (lane == 63) s_wsum[wave] = incl;
-    s_v[tid] = v;
-    s_deg[tid] = deg;
-    s_k[tid] = k;
-    s_off[tid] = o;
     __syncthreads();
     uint32_t wbase = 0, total = 0;
 #pragma unroll
@@ -237,60 +292,74 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(SampleArgs a)
     }
     __syncthreads();
     const uint32_t base = s_base;
-    const uint32_t rp = base + wbase + incl - k;
-    s_rp[tid] = rp;
-    if (i < n) a.row_ptr[i] = (int32_t)rp;
+    if (wave < 4) {
+        const uint32_t rp = base + wbase + incl - k;
+        s_rp[tid] = rp;
+        if ((uint32_t)tid < T && i < n) a.row_ptr[i] = (int32_t)rp;
+    }
     if (tile == ntiles - 1 && tid == 0) {
         a.row_ptr[n] = (int32_t)(base + total);
         d->E[a.hop] = base + total;
     }
     __syncthreads();
 
-    // ---- sampling: one group of G lanes per vertex, one lane per slot
-    const int glog = a.group_log2;
+    // ---- lane (t, gl): slot gl of the tile's vertex t
     const int G = 1 << glog;
     const int gl = lane & (G - 1);
     const int gbase = lane & ~(G - 1);
-    const unsigned long long gmask = G == 64 ? ~0ull : ((1ull << G) - 1ull);
-    const int ngroups = kBlock >> glog;
-    const int grp = (wave << (6 - glog)) + (lane >> glog);
-    const uint32_t nvalid = n - tile * kSampleTile < (uint32_t)kSampleTile ? n - tile * kSampleTile : (uint32_t)kSampleTile;
-    const uint32_t key_lo = d->key_lo, key_hi = d->key_hi;
-
-    for (int t = grp; t < kSampleTile; t += ngroups) { // same trip count for every group
-        const bool act = (uint32_t)t < nvalid;
-        const int32_t tv = s_v[t];
-        const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
-        const unsigned long long toff = s_off[t];
-        const bool slot = act && (uint32_t)gl < tk;
-        uint32_t pos = (uint32_t)gl;
-        if (a.replace) {
-            if (slot) pos = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
-        } else {
-            const bool floyd = slot && tdeg > F;
+    const int t = tid >> glog;
+    const int32_t tv = s_v[t];
+    const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
+    const unsigned long long toff = s_off[t];
+    const bool slot = (uint32_t)gl < tk;
+    uint32_t pos = (uint32_t)gl;
+    if (a.replace) {
+        if (slot) pos = (uint32_t)__umul64hi(philox_draw(d->key_lo, d->key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
+    } else {
+        const bool floyd = slot && tdeg > F;
+        if (__any(floyd)) {
+            const uint32_t tail0 = tdeg - F; // candidates >= tail0 coincide with the fallback value of slot cand-tail0
             uint32_t cand = (uint32_t)gl;
             if (floyd)
-                cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
-                                            (uint64_t)(tdeg - F + (uint32_t)gl) + 1ull);
-            pos = cand;
-            if (__any(floyd)) {
-                // slot jj takes its candidate unless an earlier slot already holds it, then it takes deg-F+jj
-                for (uint32_t jj = 1; jj < F; ++jj) {
-                    const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
-                    const bool hit = (uint32_t)gl < jj && pos == cj;
-                    const unsigned long long m = __ballot(hit);
-                    const bool taken = ((m >> gbase) & gmask) != 0ull;
-                    if ((uint32_t)gl == jj) pos = taken ? (tdeg - F + jj) : cj;
-                }
+                cand = (uint32_t)__umul64hi(philox_draw(d->key_lo, d->key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
+                                            (uint64_t)(tail0 + (uint32_t)gl) + 1ull);
+            bool dup = false;
+            for (uint32_t jj = 0; jj + 1 < F; ++jj) {
+                const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
+                dup = dup || (jj < (uint32_t)gl && cj == cand);
             }
+            dup = dup && floyd;
+            const uint32_t a_i = cand - tail0; // meaningful only when cand >= tail0
+            const bool chase = floyd && cand >= tail0 && a_i < (uint32_t)gl;
+            bool collide = dup;
+            for (uint32_t it = 0; it < F; ++it) {
+                const int ca = __shfl((int)collide, gbase + (int)(chase ? a_i : 0u), 64);
+                const bool nc = dup || (chase && ca != 0);
+                const bool changed = nc != collide;
+                collide = nc;
+                if (!__any(changed)) break;
+            }
+            pos = floyd ? (collide ? tail0 + (uint32_t)gl : cand) : (uint32_t)gl;
         }
-        if (slot) {
-            const int32_t g = a.indices[toff + pos];
-            a.nbr[trp + (uint32_t)gl] = g;
-            if ((uint32_t)g < a.num_nodes && a.local_id[g] < 0) {
-                const uint32_t w = (uint32_t)g >> 5, b = 1u << (g & 31);
-                if (!(a.bitmap[w] & b)) atomicOr(&a.bitmap[w], b);
+    }
+    if (slot) {
+        const int32_t g = a.indices[toff + pos];
+        a.nbr[trp + (uint32_t)gl] = g;
+        const uint32_t b = 1u << (g & 31);
+        if ((uint32_t)g < a.num_nodes && !(a.seen[(uint32_t)g >> 5] & b)) {
+            // first lane of the tile to insert g into the LDS set marks it (at most 1024 insertions into 2048 slots)
+            uint32_t h = ((uint32_t)g * 2654435761u) >> (32 - kSampleHashBits);
+            bool first = false;
+            for (;;) {
+                const uint32_t old = atomicCAS(&s_set[h], 0xFFFFFFFFu, (uint32_t)g);
+                if (old == 0xFFFFFFFFu) {
+                    first = true;
+                    break;
+                }
+                if (old == (uint32_t)g) break;
+                h = (h + 1) & (kSampleHashSlots - 1);
             }
+            if (first) atomicOr(&a.bitmap[(uint32_t)g >> 5], b);
         }
     }
 }
@@ -298,48 +367,41 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(SampleArgs a)
 struct CompactArgs {
     Drmb *drmb;
     uint32_t *bitmap;
+    uint32_t *seen;
     int32_t *S;
     int32_t *local_id;
     uint64_t *status;
     uint32_t cap_next;
     int32_t hop;
+    int32_t last_hop; // nothing is sampled from the vertices this hop adds: their "seen" bits are not needed
 };
 
-// Hop h, "compact / rank": the hop's bitmap of new vertices is scanned in one chained pass over
-// |V|/32 words; the rank of a set bit is n_h + (set bits before it), so the new vertices land behind
-// D_h in ascending global id and get their local id at once.  Consumed words are cleared for the next
-// hop.  Entries beyond the cap are dropped (never written) and the hop's overflow bit is raised.
+// Hop h, "compact / rank": the hop's bitmap holds exactly the new vertices (ids already in D_h never reach
+// it).  One chained pass over its |V|/32 words: the rank of a set bit is n_h + (set bits before it), so the
+// new vertices land behind D_h in ascending global id and get their local id at once.  Consumed words are
+// cleared for the next hop and their bits join "seen".  Entries beyond the cap are dropped (never written,
+// local id -1, not "seen") and the hop's overflow bit is raised.
 __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 {
     __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[4][4];
+    __shared__ uint32_t s_wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
     __syncthreads();
     const uint32_t tile = s_tile;
-    uint4 *bm = reinterpret_cast<uint4 *>(a.bitmap) + (size_t)tile * (kCompactTileWords / 4);
-    uint4 w[4];
-    uint32_t cnt[4], incl[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        w[s] = bm[s * kBlock + tid];
-        cnt[s] = __popc(w[s].x) + __popc(w[s].y) + __popc(w[s].z) + __popc(w[s].w);
-        incl[s] = wave_incl_scan(cnt[s], lane);
-        if (lane == 63) s_wsum[s][wave] = incl[s];
-    }
+    const size_t q = (size_t)tile * (kCompactTileWords / 4) + tid;
+    const uint4 m = reinterpret_cast<const uint4 *>(a.bitmap)[q];
+    const uint32_t nw[4] = {m.x, m.y, m.z, m.w};
+    const uint32_t cnt = __popc(nw[0]) + __popc(nw[1]) + __popc(nw[2]) + __popc(nw[3]);
+    const uint32_t incl = wave_incl_scan(cnt, lane);
+    if (lane == 63) s_wsum[wave] = incl;
     __syncthreads();
-    uint32_t total = 0, my_off[4];
+    uint32_t wbase = 0, total = 0;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        uint32_t wb = 0, st = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (q < wave) wb += s_wsum[s][q];
-            st += s_wsum[s][q];
-        }
-        my_off[s] = total + wb + incl[s] - cnt[s];
-        total += st;
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) wbase += s_wsum[w];
+        total += s_wsum[w];
     }
     if (wave == 0) {
         const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
@@ -348,15 +410,14 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     __syncthreads();
     const uint32_t n_h = d->n[a.hop];
     const uint32_t base = n_h + s_base;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        if (cnt[s] == 0) continue;
-        uint32_t r = base + my_off[s];
-        const uint32_t word0 = tile * kCompactTileWords + (uint32_t)(s * kBlock + tid) * 4u;
-        const uint32_t ws[4] = {w[s].x, w[s].y, w[s].z, w[s].w};
+    if (cnt) {
+        uint32_t r = base + wbase + incl - cnt;
+        const uint32_t word0 = (uint32_t)q * 4u;
+        uint32_t kept[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint32_t bits = ws[c];
+            uint32_t bits = nw[c];
+            kept[c] = 0;
             while (bits) {
                 const int b = __ffs((int)bits) - 1;
                 bits &= bits - 1;
@@ -364,11 +425,18 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
                 if (r < a.cap_next) {
                     a.S[r] = gid;
                     a.local_id[gid] = (int32_t)r;
+                    kept[c] |= 1u << b;
+                } else {
+                    a.local_id[gid] = -1;
                 }
                 ++r;
             }
         }
-        bm[s * kBlock + tid] = make_uint4(0, 0, 0, 0);
+        if (!a.last_hop) { // this lane is the only writer of these words during the kernel
+            const uint4 sn = reinterpret_cast<const uint4 *>(a.seen)[q];
+            reinterpret_cast<uint4 *>(a.seen)[q] = make_uint4(sn.x | kept[0], sn.y | kept[1], sn.z | kept[2], sn.w | kept[3]);
+        }
+        reinterpret_cast<uint4 *>(a.bitmap)[q] = make_uint4(0, 0, 0, 0);
     }
     if (tile == gridDim.x - 1 && tid == 0) {
         const uint32_t exact = base + total;
@@ -381,48 +449,25 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     }
 }
 
-struct RelabelArgs {
-    const Drmb *drmb;
-    const int32_t *nbr;
-    const int32_t *local_id;
-    int32_t *col;
-    uint32_t num_nodes;
-    int32_t hop;
-};
-
-// Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
-__global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a)
-{
-    const uint32_t E = a.drmb->E[a.hop];
-    const uint32_t e0 = blockIdx.x * kRelabelPerBlock;
-    if (e0 >= E) return;
-#pragma unroll
-    for (int u = 0; u < kRelabelPerBlock / kBlock; ++u) {
-        const uint32_t e = e0 + u * kBlock + threadIdx.x;
-        if (e < E) {
-            const int32_t g = a.nbr[e];
-            a.col[e] = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
-        }
-    }
-}
-
 struct FinishArgs {
     Drmb *drmb;
     const int32_t *S;
-    int32_t *local_id;
+    uint32_t *seen;
     uint32_t *log;
     int32_t num_hops;
+    uint32_t blocks; // workgroups given to this role (0: role absent)
 };
 
-// End of step: the id map entries of this step's vertices go back to "absent" (the map over |V| is
-// never cleared as a whole), the step is appended to the device-side log, the step counter advances.
-__global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a)
+// End of step: the "seen" words of this step's frontier vertices (everything in D_{H-1}: the seeds and
+// what hops 0..H-2 added) go back to zero - the bitmaps over |V| are never cleared as a whole - and the
+// step is appended to the device-side log; the step counter advances.
+__device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block)
 {
-    const uint32_t n = a.drmb->n[a.num_hops];
-    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t n = a.drmb->n[a.num_hops - 1];
+    const uint32_t i = block * kBlock + threadIdx.x;
     if (i < n) {
         const int32_t g = a.S[i];
-        if (g >= 0) a.local_id[g] = -1;
+        if (g >= 0) a.seen[(uint32_t)g >> 5] = 0u;
     }
     if (i == 0) {
         Drmb *d = a.drmb;
@@ -439,9 +484,9 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a)
 }
 
 struct RowArgs {
-    const float *src;      // gather: feature table; aggregate: input rows
+    const float *src;       // gather: feature table; aggregate: input rows
     float *dst;
-    const int32_t *S;      // gather: global ids
+    const int32_t *S;       // gather: global ids
     const int32_t *row_ptr; // aggregate
     const int32_t *col;     // aggregate
     const uint32_t *n_rows; // device address of the row count
@@ -451,6 +496,7 @@ struct RowArgs {
     uint32_t dimv;
     uint32_t rows;
     uint32_t max_fanout;
+    uint32_t blocks; // workgroups given to this role (the launch's first ones; 0: role absent)
 };
 
 template <int VEC> struct VecOf;
@@ -463,12 +509,17 @@ template <> struct VecOf<1> {
     static __device__ __forceinline__ float zero() { return 0.0f; }
 };
 
-// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the
-// rows as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave
-// width still fill every lane, four loads in flight per lane before the stores.
+// "Gather": X[i,:] = feat[S[i],:], sharing its launch with the edge relabel of the last hop (workgroups
+// >= a.blocks).  A gather workgroup copies `rows` consecutive output rows; lanes walk the rows as one flat
+// run of 16-byte pieces so that rows whose length is not a multiple of the wave width still fill every
+// lane, four loads in flight per lane before the stores.
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void k_gather(RowArgs a)
+__global__ __launch_bounds__(kBlock) void k_gather(RowArgs a, RelabelArgs last)
 {
+    if (blockIdx.x >= a.blocks) {
+        relabel_block(last, blockIdx.x - a.blocks);
+        return;
+    }
     typedef typename VecOf<VEC>::type T;
     __shared__ int32_t s_id[kBlock];
     const uint32_t n = *a.n_rows;
@@ -499,12 +550,17 @@ __global__ __launch_bounds__(kBlock) void k_gather(RowArgs a)
     }
 }
 
-// "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:].  A workgroup owns `rows`
-// output rows; their row_ptr slice and column ids are staged in LDS, then each lane owns one
-// (row, 16-byte column piece) pair at a time and accumulates over the row's edges in fp32.
+// "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:], sharing its launch with the end-of-
+// step clean-up (workgroups >= a.blocks).  An aggregation workgroup owns `rows` output rows; their row_ptr
+// slice and column ids are staged in LDS, then each lane owns one (row, 16-byte column piece) pair at a
+// time and accumulates over the row's edges in fp32.
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a)
+__global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
 {
+    if (blockIdx.x >= a.blocks) {
+        finish_block(fin, blockIdx.x - a.blocks);
+        return;
+    }
     typedef typename VecOf<VEC>::type T;
     extern __shared__ int32_t s_mem[];
     int32_t *s_rp = s_mem;               // [rows+1]
@@ -618,6 +674,7 @@ struct zg_plan_s {
     float *agg() const { return lay.feat_dim > 0 ? reinterpret_cast<float *>(ws + lay.off_agg) : nullptr; }
     int32_t *local_id() const { return reinterpret_cast<int32_t *>(ws + lay.off_local_id); }
     uint32_t *bitmap() const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap); }
+    uint32_t *seen() const { return reinterpret_cast<uint32_t *>(ws + lay.off_seen); }
     uint64_t *status() const { return reinterpret_cast<uint64_t *>(ws + lay.off_status); }
     uint64_t *status_sample(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_sample[h]); }
     uint64_t *status_compact(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_compact[h]); }
@@ -625,65 +682,106 @@ struct zg_plan_s {
 
 namespace {
 
-int group_log2_for(int fanout)
-{
-    int g = 0;
-    while ((1 << g) < fanout) ++g;
-    return g;
-}
-
 bool aligned16(const void *p, int64_t ld) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 4) == 0; }
 
-int launch_gather(const zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, hipStream_t st)
+RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present)
+{
+    RelabelArgs ra;
+    std::memset(&ra, 0, sizeof(ra));
+    if (!present) return ra;
+    ra.drmb = p->drmb();
+    ra.nbr = p->nbr(hop);
+    ra.local_id = p->local_id();
+    ra.col = p->col(hop);
+    ra.num_nodes = (uint32_t)p->graph->num_nodes;
+    ra.hop = hop;
+    ra.blocks = (uint32_t)((p->lay.edge_cap[hop] + kRelabelPerBlock - 1) / kRelabelPerBlock);
+    return ra;
+}
+
+FinishArgs finish_args(const zg_plan_t *p, bool present)
+{
+    FinishArgs fa;
+    std::memset(&fa, 0, sizeof(fa));
+    if (!present) return fa;
+    const int H = p->lay.num_hops;
+    fa.drmb = p->drmb();
+    fa.S = p->S();
+    fa.seen = p->seen();
+    fa.log = p->log();
+    fa.num_hops = H;
+    fa.blocks = (uint32_t)((p->lay.node_cap[H - 1] + kBlock - 1) / kBlock);
+    return fa;
+}
+
+// gather (optional) + relabel of the last hop (optional) in one launch
+int launch_gather(const zg_plan_t *p, bool with_gather, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out,
+                  bool with_relabel, hipStream_t st)
 {
     const int H = p->lay.num_hops;
-    const bool al = aligned16(d_feat, ld) && aligned16(d_out, ld_out);
-    const RowTiling t = gather_tiling(dim, al);
     RowArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.src = d_feat;
-    a.dst = d_out;
-    a.S = p->S();
-    a.n_rows = &p->drmb()->n[H];
-    a.ld_src = ld;
-    a.ld_dst = ld_out;
-    a.inv = t.inv;
-    a.dimv = t.dimv;
-    a.rows = t.rows;
-    const unsigned grid = (unsigned)((p->lay.node_cap[H] + t.rows - 1) / t.rows);
-    if (t.vec == 4)
-        hipLaunchKernelGGL(k_gather<4>, dim3(grid), dim3(kBlock), 0, st, a);
+    int vec = 1;
+    if (with_gather) {
+        const bool al = aligned16(d_feat, ld) && aligned16(d_out, ld_out);
+        const RowTiling t = gather_tiling(dim, al);
+        vec = t.vec;
+        a.src = d_feat;
+        a.dst = d_out;
+        a.S = p->S();
+        a.n_rows = &p->drmb()->n[H];
+        a.ld_src = ld;
+        a.ld_dst = ld_out;
+        a.inv = t.inv;
+        a.dimv = t.dimv;
+        a.rows = t.rows;
+        a.blocks = (uint32_t)((p->lay.node_cap[H] + t.rows - 1) / t.rows);
+    }
+    const RelabelArgs ra = relabel_args(p, H - 1, with_relabel);
+    const unsigned grid = a.blocks + ra.blocks;
+    if (grid == 0) return ZG_OK;
+    if (vec == 4)
+        hipLaunchKernelGGL(k_gather<4>, dim3(grid), dim3(kBlock), 0, st, a, ra);
     else
-        hipLaunchKernelGGL(k_gather<1>, dim3(grid), dim3(kBlock), 0, st, a);
+        hipLaunchKernelGGL(k_gather<1>, dim3(grid), dim3(kBlock), 0, st, a, ra);
     ZG_HIP(hipGetLastError());
     return ZG_OK;
 }
 
-int launch_aggregate(const zg_plan_t *p, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
-                     hipStream_t st)
+// aggregation (optional) + end-of-step clean-up (optional) in one launch
+int launch_aggregate(const zg_plan_t *p, bool with_agg, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
+                     int64_t ld_out, bool with_finish, hipStream_t st)
 {
-    const bool al = aligned16(d_in, ld_in) && aligned16(d_out, ld_out);
-    const RowTiling t = aggregate_tiling(dim, al);
     RowArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.src = d_in;
-    a.dst = d_out;
-    a.row_ptr = p->row_ptr(hop);
-    a.col = p->col(hop);
-    a.n_rows = &p->drmb()->n[hop];
-    a.n_cols = &p->drmb()->n[hop + 1];
-    a.ld_src = ld_in;
-    a.ld_dst = ld_out;
-    a.inv = t.inv;
-    a.dimv = t.dimv;
-    a.rows = t.rows;
-    a.max_fanout = (uint32_t)p->lay.fanout[hop];
-    const unsigned grid = (unsigned)((p->lay.node_cap[hop] + t.rows - 1) / t.rows);
-    const size_t lds = ((size_t)t.rows + 1 + (size_t)t.rows * a.max_fanout) * 4;
-    if (t.vec == 4)
-        hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, a);
+    int vec = 1;
+    size_t lds = 0;
+    if (with_agg) {
+        const bool al = aligned16(d_in, ld_in) && aligned16(d_out, ld_out);
+        const RowTiling t = aggregate_tiling(dim, al);
+        vec = t.vec;
+        a.src = d_in;
+        a.dst = d_out;
+        a.row_ptr = p->row_ptr(hop);
+        a.col = p->col(hop);
+        a.n_rows = &p->drmb()->n[hop];
+        a.n_cols = &p->drmb()->n[hop + 1];
+        a.ld_src = ld_in;
+        a.ld_dst = ld_out;
+        a.inv = t.inv;
+        a.dimv = t.dimv;
+        a.rows = t.rows;
+        a.max_fanout = (uint32_t)p->lay.fanout[hop];
+        a.blocks = (uint32_t)((p->lay.node_cap[hop] + t.rows - 1) / t.rows);
+        lds = ((size_t)t.rows + 1 + (size_t)t.rows * a.max_fanout) * 4;
+    }
+    const FinishArgs fa = finish_args(p, with_finish);
+    const unsigned grid = a.blocks + fa.blocks;
+    if (grid == 0) return ZG_OK;
+    if (vec == 4)
+        hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, a, fa);
     else
-        hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, a);
+        hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, a, fa);
     ZG_HIP(hipGetLastError());
     return ZG_OK;
 }
@@ -695,6 +793,7 @@ int launch_ingest(const zg_plan_t *p, const int32_t *d_seeds, uint64_t key, hipS
     a.seeds = d_seeds;
     a.S = p->S();
     a.local_id = p->local_id();
+    a.seen = p->seen();
     a.status = p->status();
     a.status_words = p->lay.status_words;
     a.batch = (uint32_t)p->batch;
@@ -716,64 +815,47 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
     const int H = L.num_hops;
     for (int h = 0; h < H; ++h) {
         SampleArgs sa;
+        std::memset(&sa, 0, sizeof(sa));
         sa.offsets = g->d_offsets;
         sa.indices = g->d_indices;
         sa.drmb = p->drmb();
         sa.S = p->S();
         sa.row_ptr = p->row_ptr(h);
         sa.nbr = p->nbr(h);
-        sa.local_id = p->local_id();
         sa.bitmap = p->bitmap();
+        sa.seen = p->seen();
         sa.status = p->status_sample(h);
         sa.num_nodes = (uint32_t)g->num_nodes;
         sa.hop = h;
         sa.fanout = L.fanout[h];
-        sa.group_log2 = group_log2_for(L.fanout[h]);
+        sa.group_log2 = sample_group_log2(L.fanout[h]);
         sa.replace = (p->flags & ZG_PLAN_REPLACE) ? 1 : 0;
-        const unsigned gs = (unsigned)L.sample_tiles[h];
+        sa.blocks = (uint32_t)L.sample_tiles[h];
+        const RelabelArgs ra = relabel_args(p, h - 1, h > 0);
+        const unsigned gs = sa.blocks + ra.blocks;
         if (g->offsets_dtype == ZG_I64)
-            hipLaunchKernelGGL(k_sample_hop<int64_t>, dim3(gs), dim3(kBlock), 0, st, sa);
+            hipLaunchKernelGGL(k_sample_hop<int64_t>, dim3(gs), dim3(kSampleBlock), 0, st, sa, ra);
         else
-            hipLaunchKernelGGL(k_sample_hop<int32_t>, dim3(gs), dim3(kBlock), 0, st, sa);
+            hipLaunchKernelGGL(k_sample_hop<int32_t>, dim3(gs), dim3(kSampleBlock), 0, st, sa, ra);
         ZG_HIP(hipGetLastError());
 
         CompactArgs ca;
         ca.drmb = p->drmb();
         ca.bitmap = p->bitmap();
+        ca.seen = p->seen();
         ca.S = p->S();
         ca.local_id = p->local_id();
         ca.status = p->status_compact(h);
         ca.cap_next = (uint32_t)L.node_cap[h + 1];
         ca.hop = h;
+        ca.last_hop = h == H - 1 ? 1 : 0;
         hipLaunchKernelGGL(k_compact_hop, dim3((unsigned)L.compact_tiles), dim3(kBlock), 0, st, ca);
         ZG_HIP(hipGetLastError());
-
-        RelabelArgs ra;
-        ra.drmb = p->drmb();
-        ra.nbr = p->nbr(h);
-        ra.local_id = p->local_id();
-        ra.col = p->col(h);
-        ra.num_nodes = (uint32_t)g->num_nodes;
-        ra.hop = h;
-        const unsigned gr = (unsigned)((L.edge_cap[h] + kRelabelPerBlock - 1) / kRelabelPerBlock);
-        hipLaunchKernelGGL(k_relabel_hop, dim3(gr), dim3(kBlock), 0, st, ra);
-        ZG_HIP(hipGetLastError());
     }
-    if (p->d_feat && L.feat_dim > 0) {
-        int rc = launch_gather(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, st);
-        if (rc != ZG_OK) return rc;
-        rc = launch_aggregate(p, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, st);
-        if (rc != ZG_OK) return rc;
-    }
-    FinishArgs fa;
-    fa.drmb = p->drmb();
-    fa.S = p->S();
-    fa.local_id = p->local_id();
-    fa.log = p->log();
-    fa.num_hops = H;
-    hipLaunchKernelGGL(k_finish, dim3((unsigned)((L.node_cap[H] + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, fa);
-    ZG_HIP(hipGetLastError());
-    return ZG_OK;
+    const bool feats = p->d_feat && L.feat_dim > 0;
+    int rc = launch_gather(p, feats, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, true, st);
+    if (rc != ZG_OK) return rc;
+    return launch_aggregate(p, feats, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, true, st);
 }
 
 void drop_graph(zg_plan_t *p)
@@ -835,10 +917,11 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
     if (hipGetDevice(&p->device) != hipSuccess) return bail(fail(ZG_EHIP, "hipGetDevice failed"));
     if (p->device != g->device) return bail(fail(ZG_ESTATE, "current device differs from the graph's device"));
 
-    // initial state: metadata and log zero, id map all "absent" (-1), bitmap and scan state zero
+    // initial state: metadata, log, both bitmaps and the scan state zero (the id map needs no initial value:
+    // an entry is only read for a vertex whose entry was written earlier in the same step)
     hipError_t e = hipMemsetAsync(p->ws + L.off_drmb, 0, sizeof(Drmb), st);
     if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_log, 0, (size_t)kLogCapacity * ZG_LOG_STRIDE * 4, st);
-    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_local_id, 0xFF, (size_t)g->num_nodes * 4, st);
+    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_seen, 0, (size_t)L.bitmap_words * 4, st);
     if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap, 0, (size_t)L.bitmap_words * 4, st);
     if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -914,7 +997,7 @@ int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float 
 {
     if (!p || !d_feat || !d_out) return fail(ZG_EINVAL, "null argument");
     if (dim < 1 || dim > 32768 || ld < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
-    return launch_gather(p, d_feat, ld, dim, d_out, ld_out, static_cast<hipStream_t>(stream));
+    return launch_gather(p, true, d_feat, ld, dim, d_out, ld_out, false, static_cast<hipStream_t>(stream));
 }
 
 int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
@@ -923,7 +1006,7 @@ int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_i
     if (!p || !d_in || !d_out) return fail(ZG_EINVAL, "null argument");
     if (hop < 0 || hop >= p->lay.num_hops) return fail(ZG_EINVAL, "hop out of range");
     if (dim < 1 || dim > 32768 || ld_in < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
-    return launch_aggregate(p, hop, d_in, ld_in, dim, d_out, ld_out, static_cast<hipStream_t>(stream));
+    return launch_aggregate(p, true, hop, d_in, ld_in, dim, d_out, ld_out, false, static_cast<hipStream_t>(stream));
 }
 
 int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag)

@@ -39,6 +39,16 @@ RowTiling aggregate_tiling(int32_t dim, bool aligned16)
     return t;
 }
 
+// frontier vertices per sampling workgroup: 1024 lanes / (lanes per vertex = power of two >= max(4, fanout))
+int sample_group_log2(int fanout)
+{
+    int g = 2;
+    while ((1 << g) < fanout) ++g;
+    return g;
+}
+
+int64_t sample_tile_nodes(int fanout) { return kSampleBlock >> sample_group_log2(fanout); }
+
 // ---- envelope ----------------------------------------------------------------------------------
 
 static int64_t sat_mul_add(int64_t n, int64_t f)
@@ -132,7 +142,7 @@ int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops
         L.edge_cap[h] = L.node_cap[h] * fanouts[h];
         if (L.edge_cap[h] >= (int64_t)1 << 31) return fail(ZG_EINVAL, "edge capacity of a hop reaches 2^31");
         pi.edge_cap[h] = L.edge_cap[h];
-        L.sample_tiles[h] = (L.node_cap[h] + kSampleTile - 1) / kSampleTile;
+        L.sample_tiles[h] = (L.node_cap[h] + sample_tile_nodes(fanouts[h]) - 1) / sample_tile_nodes(fanouts[h]);
     }
     L.bitmap_words = (int64_t)align_up((size_t)((V + 31) / 32), kCompactTileWords);
     L.compact_tiles = L.bitmap_words / kCompactTileWords;
@@ -158,6 +168,7 @@ int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops
     L.envelope_end = off;
     L.off_local_id = place((size_t)V * 4);
     L.off_bitmap = place((size_t)L.bitmap_words * 4);
+    L.off_seen = place((size_t)L.bitmap_words * 4);
     L.status_words = 0;
     for (int h = 0; h < num_hops; ++h) L.status_words += (size_t)L.sample_tiles[h] + (size_t)L.compact_tiles;
     L.off_status = place(L.status_words * 8);

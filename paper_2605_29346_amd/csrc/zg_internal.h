@@ -12,9 +12,11 @@
 namespace zg {
 
 constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts of 64)
-constexpr int kSampleTile = 256;        // frontier vertices per sampling workgroup
-constexpr int kCompactTileWords = 4096; // bitmap words per compaction workgroup (4 x uint4 per thread)
-constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup
+constexpr int kSampleBlock = 1024;      // threads per sampling workgroup: (1024 / G) frontier vertices x G slots
+constexpr int kCompactTileWords = 1024; // bitmap words per compaction workgroup (one uint4 per thread)
+constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
+constexpr int kSampleHashSlots = 1 << kSampleHashBits;
+constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup (any workgroup size)
 constexpr int kLogCapacity = 1024;      // records in the device-side step log
 constexpr size_t kAlign = 256;          // every buffer starts on a 256-byte boundary ...
 constexpr size_t kGuard = 256;          // ... and is followed by at least this many untouched bytes
@@ -47,7 +49,7 @@ struct Layout {
     size_t off_row_ptr[ZG_MAX_HOPS] = {}, off_nbr[ZG_MAX_HOPS] = {}, off_col[ZG_MAX_HOPS] = {};
     size_t off_X = 0, off_agg = 0;
     size_t envelope_end = 0;
-    size_t off_local_id = 0, off_bitmap = 0, off_status = 0;
+    size_t off_local_id = 0, off_bitmap = 0, off_seen = 0, off_status = 0;
     size_t status_words = 0; // uint64 words: sampling tiles of every hop, then compaction tiles of every hop
     size_t off_status_sample[ZG_MAX_HOPS] = {}, off_status_compact[ZG_MAX_HOPS] = {};
     size_t total = 0;
@@ -66,6 +68,8 @@ struct RowTiling {
     uint64_t inv;       // ceil(2^32 / dimv): e / dimv == (e * inv) >> 32 for the small e used
     uint32_t rows;      // rows per workgroup
 };
+int sample_group_log2(int fanout);
+int64_t sample_tile_nodes(int fanout);
 RowTiling gather_tiling(int32_t dim, bool aligned16);
 RowTiling aggregate_tiling(int32_t dim, bool aligned16);
 

@@ -99,7 +99,7 @@ def test_plan_query_max_envelope_is_eq1_hop_by_hop():
     assert info.envelope_bytes == info.maxsg_envelope_bytes
     assert info.workspace_bytes == info.envelope_bytes + info.scratch_bytes
     assert info.scratch_bytes >= 10_000 * 4 + 10_000 // 8
-    assert list(info.grid_sample[:3]) == [1, 3, 12]
+    assert list(info.grid_sample[:3]) == [1, 3, 12]  # tiles of 1024 / (lanes per vertex) = 128, 256, 256 vertices
 
 
 def test_plan_query_model_envelope_uses_margin_and_z():
