@@ -132,7 +132,7 @@ def main():
     wall, pipeline = wall_single, 1
     if args.pipeline > 1:
         plans = [plan] + [make_plan(env_mode) for _ in range(args.pipeline - 1)]
-        streams = [torch.cuda.Stream() for _ in plans]
+        streams = [zg.new_stream() for _ in plans]  # own streams: they map to distinct hardware queues
         torch.cuda.synchronize()
         wall_pipe = run(plans, streams)
         assert flags_of(plans) == 0, f"device status flags {flags_of(plans):#x}"

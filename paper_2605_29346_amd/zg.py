@@ -143,6 +143,25 @@ def make_envelope(mode: int = ENV_MAX, *, flags: int = 0, margin: float = -1.0, 
     return e
 
 
+_hip = None
+
+
+def new_stream() -> int:
+    """A fresh non-blocking hipStream_t (default priority) as an integer handle.  Streams made this way land on
+    distinct hardware queues, so steps of different plans issued on them overlap."""
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        _hip.hipStreamSynchronize.argtypes = [C.c_void_p]
+        _hip.hipStreamDestroy.argtypes = [C.c_void_p]
+    s = C.c_void_p()
+    rc = _hip.hipStreamCreateWithFlags(C.byref(s), 1)  # hipStreamNonBlocking
+    if rc != 0:
+        raise RuntimeError(f"hipStreamCreateWithFlags failed with {rc}")
+    return s.value
+
+
 def _stream_ptr(stream) -> int:
     if stream is None:
         import torch
