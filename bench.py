@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
-    ap.add_argument("--pipeline", type=int, default=2,
+    ap.add_argument("--pipeline", type=int, default=4,
                     help="independent plans replayed round-robin on their own streams (consecutive mini-batches do not "
                          "depend on each other); 1 = strictly one step after the other")
     args = ap.parse_args()
@@ -166,15 +166,21 @@ def main():
     stream = torch.cuda.current_stream()
 
     def time_kernel(fn):
+        # average launch duration: `kernel_reps` launches back to back between one pair of events on the
+        # launch stream (so the events' own cost is spread over the launches), best of 3 such runs
         fn()
         torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.kernel_reps)]
-        for a, b in evs:
+        best = None
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(stream)
-            fn()
+            for _ in range(args.kernel_reps):
+                fn()
             b.record(stream)
-        torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+            torch.cuda.synchronize()
+            t = a.elapsed_time(b) * 1e-3 / args.kernel_reps
+            best = t if best is None else min(best, t)
+        return best
 
     t_gather = time_kernel(lambda: plan.gather(feat, X[:, :cfg.dim]))
     t_agg = time_kernel(lambda: plan.aggregate_mean(H - 1, X[:, :cfg.dim], aggv[:, :cfg.dim]))

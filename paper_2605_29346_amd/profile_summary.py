@@ -18,7 +18,62 @@ def short(name: str) -> str:
     return name.split("(")[0]
 
 
+def pmc_main(argv) -> None:
+    """pmc <fetch_counter_collection.csv> <write_counter_collection.csv> [--traffic-out file] [--cmd "..."]:
+    HBM bytes per launch of the library's kernels from FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+    counter reads for the probe's calibration kernel (which reads and writes a known number of bytes)."""
+    from .traffic_probe import CALIB_BYTES, CALIB_ELEMS
+    ap = argparse.ArgumentParser()
+    ap.add_argument("fetch_csv")
+    ap.add_argument("write_csv")
+    ap.add_argument("--traffic-out", default="")
+    ap.add_argument("--cmd", default="")
+    ap.add_argument("--last", type=int, default=20, help="use the last N launches of each kernel (the timed steps)")
+    args = ap.parse_args(argv)
+
+    def load(path, counter):
+        per_kernel, calib = defaultdict(list), []
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            name, val = r["Kernel_Name"], float(r["Counter_Value"])
+            if "zg::" in name:
+                per_kernel[short(name)].append(val)
+            elif "MulFunctor<float>" in name and int(r["Grid_Size"]) in (CALIB_ELEMS // 4, CALIB_ELEMS):
+                calib.append(val)  # the probe's dst = src * 1 (torch gives each lane 4 elements)
+        return per_kernel, calib
+
+    fetch, fcal = load(args.fetch_csv, "FETCH_SIZE")
+    write, wcal = load(args.write_csv, "WRITE_SIZE")
+    assert fcal and wcal, "calibration kernel not found in the counter files"
+    f_unit = CALIB_BYTES / (sum(fcal) / len(fcal))  # bytes per counter unit
+    w_unit = CALIB_BYTES / (sum(wcal) / len(wcal))
+    print("# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary")
+    if args.cmd:
+        print(f"\ncommands: {args.cmd}")
+    print(f"\ncalibration kernel (dst = src * 1, {CALIB_BYTES} bytes read and {CALIB_BYTES} written): FETCH_SIZE reads "
+          f"{sum(fcal) / len(fcal):.1f}, WRITE_SIZE reads {sum(wcal) / len(wcal):.1f} -> {f_unit:.1f} and {w_unit:.1f} bytes per unit "
+          f"(1 KiB = 1024)")
+    print("\n| kernel | launches used | FETCH_SIZE avg | WRITE_SIZE avg | HBM read MB | HBM write MB |")
+    print("|---|---|---|---|---|---|")
+    lines = []
+    for k in sorted(fetch):
+        f = fetch[k][-args.last:]
+        w = write.get(k, [0.0])[-args.last:]
+        fb, wb = f_unit * sum(f) / len(f), w_unit * sum(w) / len(w)
+        print(f"| {k} | {len(f)} | {sum(f) / len(f):.1f} | {sum(w) / len(w):.1f} | {fb / 1e6:.2f} | {wb / 1e6:.2f} |")
+        lines.append(f"{k.split('<')[0]} {fb:.0f} {wb:.0f}")
+    if args.traffic_out:
+        with open(args.traffic_out, "w") as fh:
+            fh.write("# kernel  hbm_read_bytes_per_launch  hbm_write_bytes_per_launch  (from the summary beside this file)\n")
+            fh.write("\n".join(lines) + "\n")
+
+
 def main() -> None:
+    import sys
+    if len(sys.argv) > 1 and sys.argv[1] == "pmc":
+        pmc_main(sys.argv[2:])
+        return
     ap = argparse.ArgumentParser()
     ap.add_argument("folder")
     ap.add_argument("prefix")
