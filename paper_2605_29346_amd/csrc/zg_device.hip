@@ -206,15 +206,18 @@ struct SampleArgs {
     int32_t fanout;
     int32_t group_log2; // lanes per frontier vertex: 2^group_log2 >= max(4, fanout)
     int32_t replace;
-    uint32_t blocks;    // sampling tiles (the launch's first workgroups)
+    uint32_t tiles_per_ticket; // consecutive tiles a sampling workgroup processes
+    uint32_t blocks;    // sampling workgroups (the launch's first ones)
 };
 
 // Hop h: "row lengths", "offsets scan" and "sample" in one pass, sharing its launch with the edge relabel
-// of hop h-1 (workgroups >= sa.blocks).  A sampling workgroup has 1024 lanes and owns a tile of
-// T = 1024 / G frontier vertices, G = 2^group_log2 lanes per vertex, one lane per sampled slot, so that no
-// lane ever loops: the step is latency-bound at mini-batch sizes and the dependent chain (ticket, frontier
-// id, two offsets, chained scan, neighbor id, bitmap word) is what sets its time.  The first T lanes compute
-// k_i = min(F, deg), the tile is scanned and chained to its predecessors, row_ptr is written.  Then lane
+// of hop h-1 (workgroups >= sa.blocks).  A sampling workgroup has 1024 lanes; a tile is T = 1024 / G frontier
+// vertices, G = 2^group_log2 lanes per vertex, one lane per sampled slot, so that no lane ever loops over
+// slots: the step is latency-bound at mini-batch sizes and the dependent chain (ticket, frontier id, two
+// offsets, chained scan, neighbor id, "seen" word) is what sets its time.  A workgroup takes one ticket for
+// 1..8 consecutive tiles (more for large frontiers, to keep the ticket counter cool).  The first T lanes
+// compute k_i = min(F, deg) for all its tiles, their sum is chained to the predecessor tickets, then tile by
+// tile: local scan, row_ptr, and lane
 // (t, j) finds slot j's neighbor position of vertex t: j itself if deg <= F, else Floyd's subset algorithm
 // with one Philox draw per slot.  Floyd's "already chosen" test is sequential over the slots as written;
 // here it is resolved for all slots at once: the set before slot i always contains every earlier candidate,
@@ -240,127 +243,156 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, Relab
     __shared__ uint32_t s_set[kSampleHashSlots];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int q = tid; q < kSampleHashSlots; q += kSampleBlock) s_set[q] = 0xFFFFFFFFu;
     const int glog = a.group_log2;
     const uint32_t T = (uint32_t)kSampleBlock >> glog; // vertices per tile, 16..256
     Drmb *d = a.drmb;
     const uint32_t n = d->n[a.hop];
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop], 1u);
     __syncthreads();
-    const uint32_t tile = s_tile;
+    const uint32_t ticket = s_tile;
     const uint32_t ntiles = (n + T - 1) / T;
-    if (n == 0 && tile == 0 && tid == 0) {
+    if (n == 0 && ticket == 0 && tid == 0) {
         a.row_ptr[0] = 0;
         d->E[a.hop] = 0;
     }
-    if (tile >= ntiles) return;
-
+    const uint32_t tile0 = ticket * a.tiles_per_ticket;
+    if (tile0 >= ntiles) return;
     const uint32_t F = (uint32_t)a.fanout;
-    const uint32_t i = tile * T + (uint32_t)tid;
-    uint32_t k = 0, incl = 0;
-    if (wave < 4) { // lanes 0..255 cover the tile's vertices (T <= 256)
+    const uint32_t key_lo = d->key_lo, key_hi = d->key_hi;
+
+    // ---- pass 1: row lengths of every tile of this ticket (lanes 0..255, all loads in flight together), their
+    // sum chained to the predecessor tickets.  The ticket publishes its total before any sampling starts, so
+    // later tickets never wait for more than this pass.
+    int32_t v_[kSampleMaxTpt];
+    uint32_t deg_[kSampleMaxTpt], k_[kSampleMaxTpt];
+    unsigned long long off_[kSampleMaxTpt];
+    uint32_t ksum = 0;
+    if (wave < 4) {
         const OffT *off = (const OffT *)a.offsets;
-        int32_t v = -1;
-        uint32_t deg = 0;
-        unsigned long long o = 0;
-        if ((uint32_t)tid < T && i < n) {
-            v = a.S[i];
-            if (v >= 0) {
-                const OffT o0 = off[v], o1 = off[v + 1];
-                o = (unsigned long long)o0;
-                deg = (uint32_t)(o1 - o0);
-            }
+#pragma unroll
+        for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
+            const uint32_t i = (tile0 + sub) * T + (uint32_t)tid;
+            v_[sub] = (sub < a.tiles_per_ticket && (uint32_t)tid < T && i < n) ? a.S[i] : -1;
         }
-        k = a.replace ? (deg > 0 ? F : 0u) : (deg < F ? deg : F);
-        incl = wave_incl_scan(k, lane);
-        if (lane == 63) s_wsum[wave] = incl;
-        s_v[tid] = v;
-        s_deg[tid] = deg;
-        s_k[tid] = k;
-        s_off[tid] = o;
+#pragma unroll
+        for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
+            deg_[sub] = 0;
+            off_[sub] = 0;
+            if (v_[sub] >= 0) {
+                const OffT o0 = off[v_[sub]], o1 = off[v_[sub] + 1];
+                off_[sub] = (unsigned long long)o0;
+                deg_[sub] = (uint32_t)(o1 - o0);
+            }
+            k_[sub] = a.replace ? (deg_[sub] > 0 ? F : 0u) : (deg_[sub] < F ? deg_[sub] : F);
+            ksum += k_[sub];
+        }
+        const uint32_t wsum = wave_sum(ksum);
+        if (lane == 0) s_wsum[wave] = wsum;
     }
     __syncthreads();
-    uint32_t wbase = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        if (w < wave) wbase += s_wsum[w];
-        total += s_wsum[w];
-    }
     if (wave == 0) {
-        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
+        const uint32_t ticket_total = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+        const uint32_t e = chained_exclusive_prefix(a.status, ticket, ticket_total, &d->flags, lane);
         if (lane == 0) s_base = e;
     }
     __syncthreads();
-    const uint32_t base = s_base;
-    if (wave < 4) {
-        const uint32_t rp = base + wbase + incl - k;
-        s_rp[tid] = rp;
-        if ((uint32_t)tid < T && i < n) a.row_ptr[i] = (int32_t)rp;
-    }
-    if (tile == ntiles - 1 && tid == 0) {
-        a.row_ptr[n] = (int32_t)(base + total);
-        d->E[a.hop] = base + total;
-    }
-    __syncthreads();
+    uint32_t base = s_base;
 
-    // ---- lane (t, gl): slot gl of the tile's vertex t
-    const int G = 1 << glog;
-    const int gl = lane & (G - 1);
-    const int gbase = lane & ~(G - 1);
-    const int t = tid >> glog;
-    const int32_t tv = s_v[t];
-    const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
-    const unsigned long long toff = s_off[t];
-    const bool slot = (uint32_t)gl < tk;
-    uint32_t pos = (uint32_t)gl;
-    if (a.replace) {
-        if (slot) pos = (uint32_t)__umul64hi(philox_draw(d->key_lo, d->key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
-    } else {
-        const bool floyd = slot && tdeg > F;
-        if (__any(floyd)) {
-            const uint32_t tail0 = tdeg - F; // candidates >= tail0 coincide with the fallback value of slot cand-tail0
-            uint32_t cand = (uint32_t)gl;
-            if (floyd)
-                cand = (uint32_t)__umul64hi(philox_draw(d->key_lo, d->key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
-                                            (uint64_t)(tail0 + (uint32_t)gl) + 1ull);
-            bool dup = false;
-            for (uint32_t jj = 0; jj + 1 < F; ++jj) {
-                const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
-                dup = dup || (jj < (uint32_t)gl && cj == cand);
-            }
-            dup = dup && floyd;
-            const uint32_t a_i = cand - tail0; // meaningful only when cand >= tail0
-            const bool chase = floyd && cand >= tail0 && a_i < (uint32_t)gl;
-            bool collide = dup;
-            for (uint32_t it = 0; it < F; ++it) {
-                const int ca = __shfl((int)collide, gbase + (int)(chase ? a_i : 0u), 64);
-                const bool nc = dup || (chase && ca != 0);
-                const bool changed = nc != collide;
-                collide = nc;
-                if (!__any(changed)) break;
-            }
-            pos = floyd ? (collide ? tail0 + (uint32_t)gl : cand) : (uint32_t)gl;
+    // ---- pass 2: tile by tile
+#pragma unroll
+    for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
+        const uint32_t tile = tile0 + sub;
+        if (sub >= a.tiles_per_ticket || tile >= ntiles) break; // uniform over the workgroup
+        for (int q = tid; q < kSampleHashSlots; q += kSampleBlock) s_set[q] = 0xFFFFFFFFu;
+        const uint32_t i = tile * T + (uint32_t)tid;
+        uint32_t incl = 0;
+        if (wave < 4) {
+            incl = wave_incl_scan(k_[sub], lane);
+            if (lane == 63) s_wsum[wave] = incl;
+            s_v[tid] = v_[sub];
+            s_deg[tid] = deg_[sub];
+            s_k[tid] = k_[sub];
+            s_off[tid] = off_[sub];
         }
-    }
-    if (slot) {
-        const int32_t g = a.indices[toff + pos];
-        a.nbr[trp + (uint32_t)gl] = g;
-        const uint32_t b = 1u << (g & 31);
-        if ((uint32_t)g < a.num_nodes && !(a.seen[(uint32_t)g >> 5] & b)) {
-            // first lane of the tile to insert g into the LDS set marks it (at most 1024 insertions into 2048 slots)
-            uint32_t h = ((uint32_t)g * 2654435761u) >> (32 - kSampleHashBits);
-            bool first = false;
-            for (;;) {
-                const uint32_t old = atomicCAS(&s_set[h], 0xFFFFFFFFu, (uint32_t)g);
-                if (old == 0xFFFFFFFFu) {
-                    first = true;
-                    break;
+        __syncthreads();
+        uint32_t wbase = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) wbase += s_wsum[w];
+            total += s_wsum[w];
+        }
+        if (wave < 4) {
+            const uint32_t rp = base + wbase + incl - k_[sub];
+            s_rp[tid] = rp;
+            if ((uint32_t)tid < T && i < n) a.row_ptr[i] = (int32_t)rp;
+        }
+        if (tile == ntiles - 1 && tid == 0) {
+            a.row_ptr[n] = (int32_t)(base + total);
+            d->E[a.hop] = base + total;
+        }
+        base += total;
+        __syncthreads();
+
+        // ---- lane (t, gl): slot gl of the tile's vertex t
+        const int G = 1 << glog;
+        const int gl = lane & (G - 1);
+        const int gbase = lane & ~(G - 1);
+        const int t = tid >> glog;
+        const int32_t tv = s_v[t];
+        const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
+        const unsigned long long toff = s_off[t];
+        const bool slot = (uint32_t)gl < tk;
+        uint32_t pos = (uint32_t)gl;
+        if (a.replace) {
+            if (slot) pos = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
+        } else {
+            const bool floyd = slot && tdeg > F;
+            if (__any(floyd)) {
+                const uint32_t tail0 = tdeg - F; // candidates >= tail0 coincide with the fallback value of slot cand-tail0
+                uint32_t cand = (uint32_t)gl;
+                if (floyd)
+                    cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
+                                                (uint64_t)(tail0 + (uint32_t)gl) + 1ull);
+                bool dup = false;
+                for (uint32_t jj = 0; jj + 1 < F; ++jj) {
+                    const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
+                    dup = dup || (jj < (uint32_t)gl && cj == cand);
                 }
-                if (old == (uint32_t)g) break;
-                h = (h + 1) & (kSampleHashSlots - 1);
+                dup = dup && floyd;
+                const uint32_t a_i = cand - tail0; // meaningful only when cand >= tail0
+                const bool chase = floyd && cand >= tail0 && a_i < (uint32_t)gl;
+                bool collide = dup;
+                for (uint32_t it = 0; it < F; ++it) {
+                    const int ca = __shfl((int)collide, gbase + (int)(chase ? a_i : 0u), 64);
+                    const bool nc = dup || (chase && ca != 0);
+                    const bool changed = nc != collide;
+                    collide = nc;
+                    if (!__any(changed)) break;
+                }
+                pos = floyd ? (collide ? tail0 + (uint32_t)gl : cand) : (uint32_t)gl;
             }
-            if (first) atomicOr(&a.bitmap[(uint32_t)g >> 5], b);
         }
+        if (slot) {
+            const int32_t g = a.indices[toff + pos];
+            a.nbr[trp + (uint32_t)gl] = g;
+            const uint32_t b = 1u << (g & 31);
+            if ((uint32_t)g < a.num_nodes && !(a.seen[(uint32_t)g >> 5] & b)) {
+                // first lane of the tile to insert g into the LDS set marks it (at most 1024 insertions into 2048 slots)
+                uint32_t h = ((uint32_t)g * 2654435761u) >> (32 - kSampleHashBits);
+                bool first = false;
+                for (;;) {
+                    const uint32_t old = atomicCAS(&s_set[h], 0xFFFFFFFFu, (uint32_t)g);
+                    if (old == 0xFFFFFFFFu) {
+                        first = true;
+                        break;
+                    }
+                    if (old == (uint32_t)g) break;
+                    h = (h + 1) & (kSampleHashSlots - 1);
+                }
+                if (first) atomicOr(&a.bitmap[(uint32_t)g >> 5], b);
+            }
+        }
+        __syncthreads(); // LDS is reused by the next tile of this ticket
     }
 }
 
@@ -380,28 +412,42 @@ struct CompactArgs {
 // it).  One chained pass over its |V|/32 words: the rank of a set bit is n_h + (set bits before it), so the
 // new vertices land behind D_h in ascending global id and get their local id at once.  Consumed words are
 // cleared for the next hop and their bits join "seen".  Entries beyond the cap are dropped (never written,
-// local id -1, not "seen") and the hop's overflow bit is raised.
+// local id -1, not "seen") and the hop's overflow bit is raised.  A tile is SUB rounds of 1024 words held in
+// registers, SUB chosen by the planner so that the ticket counter sees a few hundred atomics at most.
+template <int SUB>
 __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 {
     __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[4];
+    __shared__ uint32_t s_wsum[SUB][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
     __syncthreads();
     const uint32_t tile = s_tile;
-    const size_t q = (size_t)tile * (kCompactTileWords / 4) + tid;
-    const uint4 m = reinterpret_cast<const uint4 *>(a.bitmap)[q];
-    const uint32_t nw[4] = {m.x, m.y, m.z, m.w};
-    const uint32_t cnt = __popc(nw[0]) + __popc(nw[1]) + __popc(nw[2]) + __popc(nw[3]);
-    const uint32_t incl = wave_incl_scan(cnt, lane);
-    if (lane == 63) s_wsum[wave] = incl;
-    __syncthreads();
-    uint32_t wbase = 0, total = 0;
+    // the tile = SUB rounds of 1024 words; in round s lane `tid` holds words [4 tid, 4 tid + 4) of the round
+    const size_t q0 = (size_t)tile * (SUB * kCompactSubWords / 4) + tid;
+    uint4 m[SUB];
+    uint32_t cnt[SUB], incl[SUB];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        if (w < wave) wbase += s_wsum[w];
-        total += s_wsum[w];
+    for (int s = 0; s < SUB; ++s) m[s] = reinterpret_cast<const uint4 *>(a.bitmap)[q0 + (size_t)s * kBlock];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        cnt[s] = __popc(m[s].x) + __popc(m[s].y) + __popc(m[s].z) + __popc(m[s].w);
+        incl[s] = wave_incl_scan(cnt[s], lane);
+        if (lane == 63) s_wsum[s][wave] = incl[s];
+    }
+    __syncthreads();
+    uint32_t total = 0, my_off[SUB];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        uint32_t wb = 0, st = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) wb += s_wsum[s][w];
+            st += s_wsum[s][w];
+        }
+        my_off[s] = total + wb + incl[s] - cnt[s];
+        total += st;
     }
     if (wave == 0) {
         const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
@@ -410,9 +456,13 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     __syncthreads();
     const uint32_t n_h = d->n[a.hop];
     const uint32_t base = n_h + s_base;
-    if (cnt) {
-        uint32_t r = base + wbase + incl - cnt;
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        if (cnt[s] == 0) continue;
+        const size_t q = q0 + (size_t)s * kBlock;
+        uint32_t r = base + my_off[s];
         const uint32_t word0 = (uint32_t)q * 4u;
+        const uint32_t nw[4] = {m[s].x, m[s].y, m[s].z, m[s].w};
         uint32_t kept[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -830,7 +880,8 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         sa.fanout = L.fanout[h];
         sa.group_log2 = sample_group_log2(L.fanout[h]);
         sa.replace = (p->flags & ZG_PLAN_REPLACE) ? 1 : 0;
-        sa.blocks = (uint32_t)L.sample_tiles[h];
+        sa.tiles_per_ticket = (uint32_t)L.sample_tpt[h];
+        sa.blocks = (uint32_t)L.sample_blocks[h];
         const RelabelArgs ra = relabel_args(p, h - 1, h > 0);
         const unsigned gs = sa.blocks + ra.blocks;
         if (g->offsets_dtype == ZG_I64)
@@ -849,7 +900,14 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         ca.cap_next = (uint32_t)L.node_cap[h + 1];
         ca.hop = h;
         ca.last_hop = h == H - 1 ? 1 : 0;
-        hipLaunchKernelGGL(k_compact_hop, dim3((unsigned)L.compact_tiles), dim3(kBlock), 0, st, ca);
+        const dim3 gc((unsigned)L.compact_tiles);
+        switch (L.compact_sub) {
+        case 1: hipLaunchKernelGGL(k_compact_hop<1>, gc, dim3(kBlock), 0, st, ca); break;
+        case 2: hipLaunchKernelGGL(k_compact_hop<2>, gc, dim3(kBlock), 0, st, ca); break;
+        case 4: hipLaunchKernelGGL(k_compact_hop<4>, gc, dim3(kBlock), 0, st, ca); break;
+        case 8: hipLaunchKernelGGL(k_compact_hop<8>, gc, dim3(kBlock), 0, st, ca); break;
+        default: hipLaunchKernelGGL(k_compact_hop<16>, gc, dim3(kBlock), 0, st, ca); break;
+        }
         ZG_HIP(hipGetLastError());
     }
     const bool feats = p->d_feat && L.feat_dim > 0;

@@ -143,9 +143,20 @@ int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops
         if (L.edge_cap[h] >= (int64_t)1 << 31) return fail(ZG_EINVAL, "edge capacity of a hop reaches 2^31");
         pi.edge_cap[h] = L.edge_cap[h];
         L.sample_tiles[h] = (L.node_cap[h] + sample_tile_nodes(fanouts[h]) - 1) / sample_tile_nodes(fanouts[h]);
+        // every tile takes a ticket from one device-wide counter, and same-address atomics serialise
+        // (about 15 ns each on MI355X): large frontiers give a workgroup several consecutive tiles per ticket
+        L.sample_tpt[h] = 1;
+        while (L.sample_tpt[h] < kSampleMaxTpt && L.sample_tiles[h] > (int64_t)kMaxTickets * L.sample_tpt[h]) L.sample_tpt[h] *= 2;
+        L.sample_blocks[h] = (L.sample_tiles[h] + L.sample_tpt[h] - 1) / L.sample_tpt[h];
     }
-    L.bitmap_words = (int64_t)align_up((size_t)((V + 31) / 32), kCompactTileWords);
-    L.compact_tiles = L.bitmap_words / kCompactTileWords;
+    {
+        const int64_t words = (V + 31) / 32;
+        L.compact_sub = 1;
+        while (L.compact_sub < 16 && words > (int64_t)kMaxTickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
+        const size_t tile_words = (size_t)kCompactSubWords * L.compact_sub;
+        L.bitmap_words = (int64_t)align_up((size_t)words, tile_words);
+        L.compact_tiles = L.bitmap_words / (int64_t)tile_words;
+    }
 
     size_t off = 0;
     auto place = [&](size_t bytes) {
@@ -188,7 +199,7 @@ int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops
     pi.workspace_bytes = (int64_t)L.total;
     pi.maxsg_envelope_bytes = envelope_bytes_for(pi.maxsg_nodes);
     for (int h = 0; h < num_hops; ++h) {
-        pi.grid_sample[h] = (int32_t)L.sample_tiles[h];
+        pi.grid_sample[h] = (int32_t)L.sample_blocks[h];
         pi.grid_relabel[h] = (int32_t)((L.edge_cap[h] + kRelabelPerBlock - 1) / kRelabelPerBlock);
     }
     pi.grid_compact = (int32_t)L.compact_tiles;

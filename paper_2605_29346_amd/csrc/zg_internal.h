@@ -13,7 +13,9 @@ namespace zg {
 
 constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts of 64)
 constexpr int kSampleBlock = 1024;      // threads per sampling workgroup: (1024 / G) frontier vertices x G slots
-constexpr int kCompactTileWords = 1024; // bitmap words per compaction workgroup (one uint4 per thread)
+constexpr int kCompactSubWords = 1024;  // bitmap words a compaction workgroup takes per round (one uint4 per thread)
+constexpr int kMaxTickets = 512;        // tiles are sized so that a kernel's ticket counter sees about this many atomics
+constexpr int kSampleMaxTpt = 8;        // most consecutive tiles a sampling workgroup takes per ticket
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
 constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup (any workgroup size)
@@ -42,7 +44,10 @@ struct Layout {
     int64_t edge_cap[ZG_MAX_HOPS] = {};
     int32_t fanout[ZG_MAX_HOPS] = {};
     int64_t bitmap_words = 0; // padded to whole compaction tiles
-    int64_t sample_tiles[ZG_MAX_HOPS] = {};
+    int64_t sample_tiles[ZG_MAX_HOPS] = {};   // tiles of 1024 / G frontier vertices
+    int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..8)
+    int64_t sample_blocks[ZG_MAX_HOPS] = {};  // sampling workgroups = ceil(tiles / tiles per ticket)
+    int32_t compact_sub = 1;                  // rounds of 1024 words per compaction tile (1, 2, 4, 8 or 16)
     int64_t compact_tiles = 0;
     // byte offsets into the workspace
     size_t off_drmb = 0, off_log = 0, off_S = 0;
