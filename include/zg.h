@@ -15,7 +15,8 @@
  *  - Pointers named d_* are DEVICE pointers (hipMalloc'ed or a torch CUDA tensor's data_ptr);
  *    all others are HOST pointers.  The library borrows device memory, it never frees it, and
  *    apart from zg_graph_create(ZG_GRAPH_VALIDATE) it never allocates any: the caller
- *    provides one workspace whose size zg_plan_query reports.
+ *    provides one workspace whose size zg_plan_query reports.  zg_plan additionally takes 4 KiB
+ *    of pinned host memory (hipHostMalloc) for the per-step mailbox, freed by zg_plan_destroy.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *  - Hops h = 0..H-1 count outward from the seeds.  D_h (n_h vertices) is the frontier whose
  *    neighbors hop h samples - the rows of block h; S_h = D_h followed by the hop's newly
@@ -159,6 +160,7 @@ int zg_plan_query(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops,
  * launch skeleton.  May synchronise.  The workspace belongs to the plan until zg_plan_destroy. */
 int zg_plan(zg_plan_t **p, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
             const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream);
+/* Waits for the device to go idle (a step in flight still uses the plan), then releases the plan. */
 int zg_plan_destroy(zg_plan_t *p);
 /* Makes gather + aggregation part of the step: d_feat is the [num_nodes, ld] fp32 table (row stride ld
  * elements, >= feat_dim), borrowed.  Rebuilds the captured graph; call between steps, may synchronise. */
@@ -166,10 +168,14 @@ int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld);
 int zg_plan_outputs(const zg_plan_t *p, zg_outputs *out);
 
 /* ---- per step ---------------------------------------------------------------------------------
- * One mini-batch: d_seeds = `batch` distinct vertex ids (device memory, or pinned host memory the
- * device can read), read when the step runs on `stream`.  Enqueues the ingest of (seeds, rng_key) and
- * ONE graph launch; never synchronises, never allocates.  Results are in the plan's output buffers
- * once `stream` reaches this point.  Steps of one plan must be stream-ordered one after another. */
+ * One mini-batch: d_seeds = `batch` distinct vertex ids in device memory (or pinned host memory the
+ * device can read), read when the step runs on `stream`; they must stay valid until then.  The call
+ * writes (d_seeds, rng_key) into a slot of a small ring in pinned host memory that the step's first
+ * kernel reads, and enqueues exactly ONE hipGraph launch - nothing else.  It never synchronises with
+ * the device and never allocates; only when 255 earlier steps of this plan are still unfinished does
+ * it wait, on the host, for the oldest one (a counter the device publishes in the same pinned ring).
+ * Results are in the plan's output buffers once `stream` reaches this point.  Steps of one plan must be
+ * stream-ordered one after another and issued from one host thread at a time. */
 int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
 /* Stand-alone feature gather for the plan's current S_{H-1}: d_out[i,:] = d_feat[S[i],:], i < n_H;
  * rows >= n_H of d_out are not written. */

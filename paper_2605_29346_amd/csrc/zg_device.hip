@@ -6,12 +6,15 @@
 // mini-batch sizes a launch costs about as much as the small kernels themselves.
 // Every kernel is launched with a grid fixed by the plan's capacity envelope, reads the true sizes
 // from the device-resident metadata buffer and lets surplus workgroups return at once (paper
-// sections 4.1-4.3).  Everything after the ingest is one hipGraph (section 4.4).
+// sections 4.1-4.3).  The whole step is one hipGraph (section 4.4); the step's seeds pointer and key reach it
+// through a mailbox in pinned host memory.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <new>
+#include <thread>
 
 #include "zg_internal.h"
 
@@ -116,9 +119,23 @@ __device__ __forceinline__ uint64_t philox_draw(uint32_t key_lo, uint32_t key_hi
 // =================================================================================================
 // kernels
 // =================================================================================================
+// Per-step inputs travel through a ring in pinned host memory that the device reads directly: the captured
+// graph's arguments are frozen, and a step must be exactly one graph launch.  The host writes slot
+// (steps issued % kMailboxSlots) before it launches the graph; the ingest kernel of step number e (the
+// device-side step counter) reads slot e % kMailboxSlots; the last kernel of a step publishes e + 1 in
+// `completed`, which the host checks (no device synchronisation) before it reuses a slot.
+struct Mailbox {
+    uint32_t completed;
+    uint32_t pad[3];
+    struct {
+        unsigned long long seeds; // device address of the step's seed ids
+        unsigned long long key;   // step key
+    } slot[kMailboxSlots];
+};
+
 struct IngestArgs {
     Drmb *drmb;
-    const int32_t *seeds;
+    const Mailbox *mailbox;
     int32_t *S;
     int32_t *local_id;
     uint32_t *seen;
@@ -126,7 +143,6 @@ struct IngestArgs {
     uint64_t status_words;
     uint32_t batch;
     uint32_t num_nodes;
-    uint32_t key_lo, key_hi;
 };
 
 // Step entry: seeds -> D_0 (caller's order), their local ids and "seen" bits; step key and counters ->
@@ -134,20 +150,28 @@ struct IngestArgs {
 // neighbors); a seed whose "seen" bit is already set is a duplicate.
 __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
 {
+    __shared__ unsigned long long s_in[2];
     const uint32_t gtid = blockIdx.x * kBlock + threadIdx.x;
     const uint32_t gsize = gridDim.x * kBlock;
+    if (threadIdx.x == 0) { // one read of the host-resident slot per workgroup
+        const uint32_t slot = a.drmb->epoch % kMailboxSlots;
+        s_in[0] = __hip_atomic_load(&a.mailbox->slot[slot].seeds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        s_in[1] = __hip_atomic_load(&a.mailbox->slot[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    __syncthreads();
+    const int32_t *seeds = reinterpret_cast<const int32_t *>(s_in[0]);
     if (gtid == 0) {
         Drmb *d = a.drmb;
         d->n[0] = a.batch;
         d->n_exact[0] = a.batch;
-        d->key_lo = a.key_lo;
-        d->key_hi = a.key_hi;
+        d->key_lo = (uint32_t)(s_in[1] & 0xFFFFFFFFull);
+        d->key_hi = (uint32_t)(s_in[1] >> 32);
         d->step_flags = 0;
         for (int i = 0; i < 2 * ZG_MAX_HOPS; ++i) d->ticket[i] = 0;
     }
     for (uint64_t w = gtid; w < a.status_words; w += gsize) a.status[w] = 0;
     if (gtid < a.batch) {
-        int32_t v = a.seeds[gtid];
+        int32_t v = seeds[gtid];
         if ((uint32_t)v >= a.num_nodes) {
             atomicOr(&a.drmb->flags, ZG_FLAG_SEED_RANGE);
             atomicOr(&a.drmb->step_flags, ZG_FLAG_SEED_RANGE);
@@ -501,6 +525,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 
 struct FinishArgs {
     Drmb *drmb;
+    Mailbox *mailbox;
     const int32_t *S;
     uint32_t *seen;
     uint32_t *log;
@@ -530,6 +555,7 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         for (int h = 0; h < a.num_hops; ++h) rec[p++] = d->E[h];
         for (int h = 1; h <= a.num_hops; ++h) rec[p++] = d->n_exact[h];
         d->epoch = epoch + 1;
+        __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -710,6 +736,9 @@ struct zg_plan_s {
     int device = -1;
     const float *d_feat = nullptr;
     int64_t ld_feat = 0;
+    Mailbox *mailbox = nullptr;     // pinned host memory
+    Mailbox *mailbox_dev = nullptr; // the same memory as the device addresses it
+    uint32_t issued = 0;            // steps enqueued so far (mod 2^32, like the device-side step counter)
     hipStream_t capture_stream = nullptr;
     hipGraph_t graph_obj = nullptr;
     hipGraphExec_t graph_exec = nullptr;
@@ -756,6 +785,7 @@ FinishArgs finish_args(const zg_plan_t *p, bool present)
     if (!present) return fa;
     const int H = p->lay.num_hops;
     fa.drmb = p->drmb();
+    fa.mailbox = p->mailbox_dev;
     fa.S = p->S();
     fa.seen = p->seen();
     fa.log = p->log();
@@ -836,11 +866,11 @@ int launch_aggregate(const zg_plan_t *p, bool with_agg, int hop, const float *d_
     return ZG_OK;
 }
 
-int launch_ingest(const zg_plan_t *p, const int32_t *d_seeds, uint64_t key, hipStream_t st)
+int launch_ingest(const zg_plan_t *p, hipStream_t st)
 {
     IngestArgs a;
     a.drmb = p->drmb();
-    a.seeds = d_seeds;
+    a.mailbox = p->mailbox_dev;
     a.S = p->S();
     a.local_id = p->local_id();
     a.seen = p->seen();
@@ -848,8 +878,6 @@ int launch_ingest(const zg_plan_t *p, const int32_t *d_seeds, uint64_t key, hipS
     a.status_words = p->lay.status_words;
     a.batch = (uint32_t)p->batch;
     a.num_nodes = (uint32_t)p->graph->num_nodes;
-    a.key_lo = (uint32_t)(key & 0xFFFFFFFFull);
-    a.key_hi = (uint32_t)(key >> 32);
     const uint64_t work = std::max<uint64_t>((uint64_t)p->batch, std::min<uint64_t>(a.status_words, 1u << 16));
     const unsigned grid = (unsigned)((work + kBlock - 1) / kBlock);
     hipLaunchKernelGGL(k_ingest, dim3(grid), dim3(kBlock), 0, st, a);
@@ -857,12 +885,14 @@ int launch_ingest(const zg_plan_t *p, const int32_t *d_seeds, uint64_t key, hipS
     return ZG_OK;
 }
 
-// everything of a step after the ingest, in order, on one stream (captured once, or issued eagerly)
+// a whole step, in order, on one stream (captured once, or issued eagerly)
 int enqueue_body(const zg_plan_t *p, hipStream_t st)
 {
     const Layout &L = p->lay;
     const zg_graph_t *g = p->graph;
     const int H = L.num_hops;
+    int rc0 = launch_ingest(p, st);
+    if (rc0 != ZG_OK) return rc0;
     for (int h = 0; h < H; ++h) {
         SampleArgs sa;
         std::memset(&sa, 0, sizeof(sa));
@@ -974,6 +1004,15 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
     };
     if (hipGetDevice(&p->device) != hipSuccess) return bail(fail(ZG_EHIP, "hipGetDevice failed"));
     if (p->device != g->device) return bail(fail(ZG_ESTATE, "current device differs from the graph's device"));
+    {
+        void *host = nullptr, *dev = nullptr;
+        if (hipHostMalloc(&host, sizeof(Mailbox), hipHostMallocDefault) != hipSuccess)
+            return bail(fail(ZG_ENOMEM, "hipHostMalloc of the step mailbox failed"));
+        std::memset(host, 0, sizeof(Mailbox));
+        p->mailbox = static_cast<Mailbox *>(host);
+        if (hipHostGetDevicePointer(&dev, host, 0) != hipSuccess) return bail(fail(ZG_EHIP, "hipHostGetDevicePointer failed"));
+        p->mailbox_dev = static_cast<Mailbox *>(dev);
+    }
 
     // initial state: metadata, log, both bitmaps and the scan state zero (the id map needs no initial value:
     // an entry is only read for a vertex whose entry was written earlier in the same step)
@@ -994,8 +1033,10 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
 int zg_plan_destroy(zg_plan_t *p)
 {
     if (!p) return ZG_OK;
+    (void)hipDeviceSynchronize(); // a step still in flight reads the mailbox and the graph
     drop_graph(p);
     if (p->capture_stream) (void)hipStreamDestroy(p->capture_stream);
+    if (p->mailbox) (void)hipHostFree(p->mailbox);
     delete p;
     return ZG_OK;
 }
@@ -1043,12 +1084,26 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
 {
     if (!p || !d_seeds) return fail(ZG_EINVAL, "null argument");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int rc = launch_ingest(p, d_seeds, rng_key, st);
-    if (rc != ZG_OK) return rc;
-    if (p->flags & ZG_PLAN_EAGER) return enqueue_body(p, st);
-    if (!p->graph_exec) return fail(ZG_ESTATE, "plan has no captured graph");
-    ZG_HIP(hipGraphLaunch(p->graph_exec, st));
-    return ZG_OK;
+    // back-pressure without touching the device: wait (host only) while every mailbox slot is taken by a
+    // step that has not finished yet
+    volatile uint32_t *done = &p->mailbox->completed;
+    while ((uint32_t)(p->issued - *done) >= (uint32_t)kMailboxSlots - 1u) std::this_thread::yield();
+    const uint32_t slot = p->issued % kMailboxSlots;
+    p->mailbox->slot[slot].seeds = reinterpret_cast<unsigned long long>(d_seeds);
+    p->mailbox->slot[slot].key = rng_key;
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+    p->issued += 1;
+    int rc = ZG_OK;
+    if (p->flags & ZG_PLAN_EAGER) {
+        rc = enqueue_body(p, st);
+    } else if (!p->graph_exec) {
+        rc = fail(ZG_ESTATE, "plan has no captured graph");
+    } else {
+        hipError_t e = hipGraphLaunch(p->graph_exec, st);
+        if (e != hipSuccess) rc = fail(ZG_EHIP, std::string("hipGraphLaunch: ") + hipGetErrorString(e));
+    }
+    if (rc != ZG_OK) p->issued -= 1; // nothing was enqueued: the slot is free again
+    return rc;
 }
 
 int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, void *stream)

@@ -19,6 +19,7 @@ constexpr int kSampleMaxTpt = 8;        // most consecutive tiles a sampling wor
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
 constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup (any workgroup size)
+constexpr int kMailboxSlots = 256;      // per-step inputs in flight between host and device
 constexpr int kLogCapacity = 1024;      // records in the device-side step log
 constexpr size_t kAlign = 256;          // every buffer starts on a 256-byte boundary ...
 constexpr size_t kGuard = 256;          // ... and is followed by at least this many untouched bytes
