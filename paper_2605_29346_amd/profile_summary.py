@@ -69,10 +69,42 @@ def pmc_main(argv) -> None:
             fh.write("\n".join(lines) + "\n")
 
 
+def hipapi_main(argv) -> None:
+    """hipapi <hip_api_trace.csv> [--warmup W] [--cmd "..."]: the HIP API calls the host makes between the first
+    and the last timed step of bench.py (every step is one hipGraphLaunch): shows that the steady-state loop
+    contains no synchronising call, no copy and no allocation."""
+    ap = argparse.ArgumentParser()
+    ap.add_argument("trace_csv")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--cmd", default="")
+    args = ap.parse_args(argv)
+    rows = sorted(csv.DictReader(open(args.trace_csv)), key=lambda r: int(r["Start_Timestamp"]))
+    launches = [i for i, r in enumerate(rows) if r["Function"] == "hipGraphLaunch"]
+    print("# rocprofv3 --hip-trace summary: host API calls inside the timed loop")
+    if args.cmd:
+        print(f"\ncommand: `{args.cmd}`")
+    print(f"\nhipGraphLaunch calls in the run: {len(launches)} ({args.warmup} warm-up steps left out below)")
+    a, b = launches[args.warmup], launches[-1]
+    inside = defaultdict(int)
+    for r in rows[a:b + 1]:
+        inside[r["Function"]] += 1
+    print("\n| HIP API call between the first and the last timed launch | calls |")
+    print("|---|---|")
+    for k, v in sorted(inside.items(), key=lambda kv: -kv[1]):
+        print(f"| {k} | {v} |")
+    sync = [k for k in inside if "Synchronize" in k or "Memcpy" in k or "Malloc" in k or k.startswith("hipEventQuery")]
+    print(f"\nsynchronising / copying / allocating calls inside the loop: {sync if sync else 'none'}")
+    print(f"first call after the loop: {rows[b + 1]['Function'] if b + 1 < len(rows) else '-'} ... "
+          f"{next((r['Function'] for r in rows[b + 1:] if 'Synchronize' in r['Function']), '-')} (the one sync that ends the timed region)")
+
+
 def main() -> None:
     import sys
     if len(sys.argv) > 1 and sys.argv[1] == "pmc":
         pmc_main(sys.argv[2:])
+        return
+    if len(sys.argv) > 1 and sys.argv[1] == "hipapi":
+        hipapi_main(sys.argv[2:])
         return
     ap = argparse.ArgumentParser()
     ap.add_argument("folder")
