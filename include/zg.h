@@ -52,6 +52,7 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
 /* zg_envelope.flags */
 #define ZG_PLAN_EAGER 1u   /* launch the step's kernels one by one instead of replaying a hipGraph */
 #define ZG_PLAN_REPLACE 2u /* sample with replacement (the setting of the paper's Lemma 1) */
+#define ZG_PLAN_SAFE_TWIN 4u /* also provision the worst-case twin of the plan: the paper's "cached safe graph" (section 4.3) */
 
 /* bits of the sticky device status word (zg_overflow_flag) */
 #define ZG_FLAG_HOP_OVERFLOW(h) (1u << (h)) /* |S_h| exceeded its cap at hop h: outputs of the step invalid */
@@ -94,6 +95,7 @@ typedef struct {
     int32_t grid_relabel[ZG_MAX_HOPS];
     int32_t grid_gather;
     int32_t grid_aggregate;
+    int64_t safe_envelope_bytes;          /* ZG_PLAN_SAFE_TWIN: bytes of the twin's outputs (part of workspace_bytes), else 0 */
 } zg_plan_info;
 
 /* Device addresses of a plan's outputs; fixed for the plan's lifetime (section 4.4, "stable buffers"). */
@@ -184,6 +186,18 @@ int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float 
  * over row i (0 for an empty row), i < n_hop. */
 int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
                       int64_t ld_out, void *stream);
+/* Overflow-safe fallback (section 4.3): replays the same mini-batch on the plan's worst-case twin (needs
+ * ZG_PLAN_SAFE_TWIN).  Same contract as zg_step; because the random draws are keyed by (key, hop, vertex,
+ * slot), the twin produces exactly what the tight plan would have produced without the overflow.  Its
+ * outputs live in the twin's own buffers (zg_plan_outputs_safe); the scratch state is shared, so the call
+ * must be stream-ordered with the plan's other steps. */
+int zg_step_safe(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
+int zg_plan_outputs_safe(const zg_plan_t *p, zg_outputs *out);
+/* Host only, no device call: how many steps of this plan have finished, and the ZG_FLAG_* bits the last
+ * finished step raised (0 = its outputs are valid).  Both come from pinned host memory that the last kernel
+ * of every step writes, so a caller that already knows step k has finished (its own event or sync) can
+ * decide about the fallback without reading device memory. */
+int zg_step_status(const zg_plan_t *p, uint32_t *steps_completed, uint32_t *last_flags);
 /* Device address of the sticky status word (ZG_FLAG_*).  The caller reads it when it chooses. */
 int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag);
 int zg_overflow_clear(zg_plan_t *p, void *stream);

@@ -127,6 +127,7 @@ __device__ __forceinline__ uint64_t philox_draw(uint32_t key_lo, uint32_t key_hi
 struct Mailbox {
     uint32_t completed;
     uint32_t pad[3];
+    uint32_t status[kMailboxSlots]; // ZG_FLAG_* bits raised by the step that used the slot
     struct {
         unsigned long long seeds; // device address of the step's seed ids
         unsigned long long key;   // step key
@@ -555,7 +556,8 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         for (int h = 0; h < a.num_hops; ++h) rec[p++] = d->E[h];
         for (int h = 1; h <= a.num_hops; ++h) rec[p++] = d->n_exact[h];
         d->epoch = epoch + 1;
-        __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&a.mailbox->status[epoch % kMailboxSlots], d->step_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -739,6 +741,7 @@ struct zg_plan_s {
     Mailbox *mailbox = nullptr;     // pinned host memory
     Mailbox *mailbox_dev = nullptr; // the same memory as the device addresses it
     uint32_t issued = 0;            // steps enqueued so far (mod 2^32, like the device-side step counter)
+    zg_plan_s *twin = nullptr;      // worst-case twin (ZG_PLAN_SAFE_TWIN): own outputs, metadata and mailbox, shared scratch
     hipStream_t capture_stream = nullptr;
     hipGraph_t graph_obj = nullptr;
     hipGraphExec_t graph_exec = nullptr;
@@ -977,27 +980,16 @@ int build_graph(zg_plan_t *p)
 
 extern "C" {
 
-int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
-            const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream)
+static int make_plan_object(zg_plan_t **out, const zg_graph_t *g, const Layout &L, uint32_t flags, int32_t batch,
+                            char *ws, hipStream_t st, bool init_scratch)
 {
-    if (!out) return fail(ZG_EINVAL, "null handle pointer");
-    *out = nullptr;
-    if (!g || g->stats_only) return fail(ZG_ESTATE, "zg_plan needs a graph handle with device arrays");
-    Layout L;
-    int rc = compute_layout(g, fanouts, num_hops, batch, env, feat_dim, nullptr, &L);
-    if (rc != ZG_OK) return rc;
-    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
-        return fail(ZG_EINVAL, "workspace must be a 256-byte aligned device pointer");
-    if (workspace_bytes < L.total) return fail(ZG_ENOMEM, "workspace smaller than zg_plan_query's workspace_bytes");
-
     zg_plan_t *p = new (std::nothrow) zg_plan_t();
     if (!p) return fail(ZG_ENOMEM, "out of host memory");
     p->graph = g;
     p->lay = L;
-    p->ws = static_cast<char *>(d_workspace);
-    p->flags = env->flags;
+    p->ws = ws;
+    p->flags = flags;
     p->batch = batch;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     auto bail = [&](int code) {
         zg_plan_destroy(p);
         return code;
@@ -1013,19 +1005,49 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
         if (hipHostGetDevicePointer(&dev, host, 0) != hipSuccess) return bail(fail(ZG_EHIP, "hipHostGetDevicePointer failed"));
         p->mailbox_dev = static_cast<Mailbox *>(dev);
     }
-
     // initial state: metadata, log, both bitmaps and the scan state zero (the id map needs no initial value:
     // an entry is only read for a vertex whose entry was written earlier in the same step)
     hipError_t e = hipMemsetAsync(p->ws + L.off_drmb, 0, sizeof(Drmb), st);
     if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_log, 0, (size_t)kLogCapacity * ZG_LOG_STRIDE * 4, st);
-    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_seen, 0, (size_t)L.bitmap_words * 4, st);
-    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap, 0, (size_t)L.bitmap_words * 4, st);
-    if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
+    if (init_scratch) {
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_seen, 0, (size_t)L.bitmap_words * 4, st);
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap, 0, (size_t)L.bitmap_words * 4, st);
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return bail(fail(ZG_EHIP, std::string("initialising the workspace: ") + hipGetErrorString(e)));
-
-    rc = build_graph(p);
+    int rc = build_graph(p);
     if (rc != ZG_OK) return bail(rc);
+    *out = p;
+    return ZG_OK;
+}
+
+int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+            const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out) return fail(ZG_EINVAL, "null handle pointer");
+    *out = nullptr;
+    if (!g || g->stats_only) return fail(ZG_ESTATE, "zg_plan needs a graph handle with device arrays");
+    Layout L, Ls;
+    int rc = compute_layout(g, fanouts, num_hops, batch, env, feat_dim, nullptr, &L, &Ls);
+    if (rc != ZG_OK) return rc;
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0)
+        return fail(ZG_EINVAL, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < L.total) return fail(ZG_ENOMEM, "workspace smaller than zg_plan_query's workspace_bytes");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(d_workspace);
+    const bool with_twin = (env->flags & ZG_PLAN_SAFE_TWIN) != 0;
+    zg_plan_t *p = nullptr;
+    // with a twin the shared scratch is sized and cleared through the twin's (larger) layout
+    rc = make_plan_object(&p, g, L, env->flags, batch, ws, st, !with_twin);
+    if (rc != ZG_OK) return rc;
+    if (with_twin) {
+        rc = make_plan_object(&p->twin, g, Ls, env->flags & ~ZG_PLAN_SAFE_TWIN, batch, ws, st, true);
+        if (rc != ZG_OK) {
+            zg_plan_destroy(p);
+            return rc;
+        }
+    }
     *out = p;
     return ZG_OK;
 }
@@ -1034,6 +1056,7 @@ int zg_plan_destroy(zg_plan_t *p)
 {
     if (!p) return ZG_OK;
     (void)hipDeviceSynchronize(); // a step still in flight reads the mailbox and the graph
+    if (p->twin) zg_plan_destroy(p->twin);
     drop_graph(p);
     if (p->capture_stream) (void)hipStreamDestroy(p->capture_stream);
     if (p->mailbox) (void)hipHostFree(p->mailbox);
@@ -1048,7 +1071,9 @@ int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld)
     if (!d_feat || ld < p->lay.feat_dim) return fail(ZG_EINVAL, "null feature table or ld < feat_dim");
     p->d_feat = d_feat;
     p->ld_feat = ld;
-    return build_graph(p);
+    int rc = build_graph(p);
+    if (rc == ZG_OK && p->twin) rc = zg_plan_bind_features(p->twin, d_feat, ld);
+    return rc;
 }
 
 int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
@@ -1104,6 +1129,31 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     }
     if (rc != ZG_OK) p->issued -= 1; // nothing was enqueued: the slot is free again
     return rc;
+}
+
+int zg_step_safe(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream)
+{
+    if (!p) return fail(ZG_EINVAL, "null plan");
+    if (!p->twin) return fail(ZG_ESTATE, "plan was made without ZG_PLAN_SAFE_TWIN");
+    return zg_step(p->twin, d_seeds, rng_key, stream);
+}
+
+int zg_plan_outputs_safe(const zg_plan_t *p, zg_outputs *out)
+{
+    if (!p) return fail(ZG_EINVAL, "null plan");
+    if (!p->twin) return fail(ZG_ESTATE, "plan was made without ZG_PLAN_SAFE_TWIN");
+    return zg_plan_outputs(p->twin, out);
+}
+
+int zg_step_status(const zg_plan_t *p, uint32_t *steps_completed, uint32_t *last_flags)
+{
+    if (!p || !steps_completed || !last_flags) return fail(ZG_EINVAL, "null argument");
+    const volatile Mailbox *m = p->mailbox;
+    const uint32_t done = m->completed;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    *steps_completed = done;
+    *last_flags = done ? m->status[(done - 1) % kMailboxSlots] : 0u;
+    return ZG_OK;
 }
 
 int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, void *stream)

@@ -57,8 +57,69 @@ static int64_t sat_mul_add(int64_t n, int64_t f)
     return n * (1 + f);
 }
 
+static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+                              const zg_envelope *env, int32_t feat_dim, zg_plan_info *info, Layout *lay);
+
+// moves a stand-alone layout: outputs to `env_base`, scratch to `scratch_base`
+static void relocate(Layout &L, size_t env_base, size_t scratch_base)
+{
+    const size_t old_scratch = L.envelope_end;
+    auto env = [&](size_t &o) { o += env_base; };
+    auto scr = [&](size_t &o) { o = scratch_base + (o - old_scratch); };
+    env(L.off_drmb);
+    env(L.off_log);
+    env(L.off_S);
+    for (int h = 0; h < L.num_hops; ++h) {
+        env(L.off_row_ptr[h]);
+        env(L.off_nbr[h]);
+        env(L.off_col[h]);
+    }
+    if (L.feat_dim > 0) {
+        env(L.off_X);
+        env(L.off_agg);
+    }
+    scr(L.off_local_id);
+    scr(L.off_bitmap);
+    scr(L.off_seen);
+    scr(L.off_status);
+    for (int h = 0; h < L.num_hops; ++h) {
+        scr(L.off_status_sample[h]);
+        scr(L.off_status_compact[h]);
+    }
+}
+
 int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
-                   int32_t feat_dim, zg_plan_info *info, Layout *lay)
+                   int32_t feat_dim, zg_plan_info *info, Layout *lay, Layout *lay_safe)
+{
+    zg_plan_info pi;
+    Layout L;
+    int rc = compute_layout_one(g, fanouts, num_hops, batch, env, feat_dim, &pi, &L);
+    if (rc != ZG_OK) return rc;
+    if (env->flags & ZG_PLAN_SAFE_TWIN) {
+        zg_envelope worst = *env;
+        worst.mode = ZG_ENV_MAX;
+        zg_plan_info pis;
+        Layout Ls;
+        rc = compute_layout_one(g, fanouts, num_hops, batch, &worst, feat_dim, &pis, &Ls);
+        if (rc != ZG_OK) return rc;
+        // [plan outputs][twin outputs][scratch, sized for the twin (it has the larger scan state)]
+        const size_t env_t = L.envelope_end, env_s = Ls.envelope_end;
+        const size_t scratch_bytes = Ls.total - Ls.envelope_end;
+        relocate(L, 0, env_t + env_s);
+        relocate(Ls, env_t, env_t + env_s);
+        L.total = Ls.total = env_t + env_s + scratch_bytes;
+        pi.safe_envelope_bytes = (int64_t)env_s;
+        pi.scratch_bytes = (int64_t)scratch_bytes;
+        pi.workspace_bytes = (int64_t)L.total;
+        if (lay_safe) *lay_safe = Ls;
+    }
+    if (info) *info = pi;
+    if (lay) *lay = L;
+    return ZG_OK;
+}
+
+static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+                              const zg_envelope *env, int32_t feat_dim, zg_plan_info *info, Layout *lay)
 {
     if (!g || !fanouts || !env) return fail(ZG_EINVAL, "null argument");
     if (num_hops < 1 || num_hops > ZG_MAX_HOPS) return fail(ZG_EINVAL, "num_hops must be in 1..ZG_MAX_HOPS");

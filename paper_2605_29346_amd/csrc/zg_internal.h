@@ -64,8 +64,10 @@ struct Layout {
 void set_error(const std::string &msg);
 int fail(int status, const std::string &msg);
 
+// `lay_safe` (optional) receives the layout of the worst-case twin when env->flags has ZG_PLAN_SAFE_TWIN: its
+// outputs sit behind the plan's own, both share one scratch region; lay->total is the whole workspace.
 int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
-                   int32_t feat_dim, zg_plan_info *info, Layout *lay);
+                   int32_t feat_dim, zg_plan_info *info, Layout *lay, Layout *lay_safe = nullptr);
 
 // launch shapes of the feature kernels for a row of `dim` floats
 struct RowTiling {

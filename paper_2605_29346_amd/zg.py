@@ -17,7 +17,7 @@ LOG_STRIDE = 32
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 I32, I64 = 0, 1
 GRAPH_VALIDATE = 1
-PLAN_EAGER, PLAN_REPLACE = 1, 2
+PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN = 1, 2, 4
 ENV_MAX, ENV_MODEL, ENV_EXPLICIT = 0, 1, 2
 FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
 
@@ -31,7 +31,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libzg.so")
 EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_stats", "zg_graph_destroy",
            "zg_graph_degree_histogram", "zg_normal_quantile", "zg_envelope_model", "zg_plan_query", "zg_plan",
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
-           "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear"]
+           "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
+           "zg_step_status"]
 
 
 class Envelope(C.Structure):
@@ -48,7 +49,8 @@ class PlanInfo(C.Structure):
                 ("envelope_bytes", C.c_int64), ("scratch_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("maxsg_envelope_bytes", C.c_int64),
                 ("grid_sample", C.c_int32 * MAX_HOPS), ("grid_compact", C.c_int32),
-                ("grid_relabel", C.c_int32 * MAX_HOPS), ("grid_gather", C.c_int32), ("grid_aggregate", C.c_int32)]
+                ("grid_relabel", C.c_int32 * MAX_HOPS), ("grid_gather", C.c_int32), ("grid_aggregate", C.c_int32),
+                ("safe_envelope_bytes", C.c_int64)]
 
 
 class Outputs(C.Structure):
@@ -96,6 +98,9 @@ def lib() -> C.CDLL:
         L.zg_aggregate_mean.argtypes = [vp, i32, vp, i64, i32, vp, i64, vp]
         L.zg_overflow_flag.argtypes = [vp, P(vp)]
         L.zg_overflow_clear.argtypes = [vp, vp]
+        L.zg_step_safe.argtypes = [vp, vp, u64, vp]
+        L.zg_plan_outputs_safe.argtypes = [vp, P(Outputs)]
+        L.zg_step_status.argtypes = [vp, P(u32), P(u32)]
         for name in EXPORTS:
             if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile"):
                 getattr(L, name).restype = C.c_int
@@ -280,6 +285,25 @@ class Plan:
     def step(self, seeds, rng_key: int, stream=None) -> None:
         """Enqueue one mini-batch (seeds: int32 CUDA tensor of `batch` distinct ids); returns at once."""
         _check(lib().zg_step(self._h, seeds.data_ptr(), C.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), _stream_ptr(stream)))
+
+    def step_safe(self, seeds, rng_key: int, stream=None) -> None:
+        """Replay the same mini-batch on the worst-case twin (plan made with PLAN_SAFE_TWIN)."""
+        _check(lib().zg_step_safe(self._h, seeds.data_ptr(), C.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), _stream_ptr(stream)))
+
+    def step_status(self):
+        """(steps finished, flags of the last finished step) read from pinned host memory: no device call."""
+        done, flags = C.c_uint32(), C.c_uint32()
+        _check(lib().zg_step_status(self._h, C.byref(done), C.byref(flags)))
+        return done.value, flags.value
+
+    def safe_view(self) -> "Plan":
+        """A Plan-like object whose views/read_step address the twin's outputs."""
+        import copy
+        twin = copy.copy(self)
+        twin.out = Outputs()
+        _check(lib().zg_plan_outputs_safe(self._h, C.byref(twin.out)))
+        twin._h = C.c_void_p()  # the view owns nothing
+        return twin
 
     def gather(self, feat, out, stream=None) -> None:
         _check(lib().zg_gather(self._h, feat.data_ptr(), feat.stride(0), feat.shape[1], out.data_ptr(), out.stride(0),

@@ -228,3 +228,51 @@ def test_api_errors():
     bad[0] = 5000
     with pytest.raises(zg.ZgError):
         zg.Graph(g.offsets.cuda(), bad.cuda(), validate=True)
+
+
+def test_safe_twin_fallback_reproduces_the_untruncated_step(oracle):
+    # the "cached safe graph": a tight plan with a worst-case twin; an overflowing batch is replayed on the twin
+    g = W.rmat_graph(30_000, 600_000, 21)
+    og = to_host_graph(oracle, g)
+    feat = W.feature_table(30_000, 20, 4)
+    pool = W.SeedPool(g, 300, 2)
+    seeds0, seeds1 = pool.batch_for(0).numpy(), pool.batch_for(1).numpy()
+    ref0 = og.sample_blocks(seeds0, (8, 6), 900)
+    ref1 = og.sample_blocks(seeds1, (8, 6), 901)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    # caps that fit batch 1 but not batch 0 at the last hop (if batch 0 is the larger one; else swap roles)
+    big, small = (0, 1) if ref0.n[2] > ref1.n[2] else (1, 0)
+    refs, seeds = [ref0, ref1], [seeds0, seeds1]
+    caps = [0, max(ref0.n[1], ref1.n[1]), refs[small].n[2] + (refs[big].n[2] - refs[small].n[2]) // 2]
+    env = zg.make_envelope(zg.ENV_EXPLICIT, flags=zg.PLAN_SAFE_TWIN, node_caps=caps)
+    plan = zg.Plan(dg, (8, 6), 300, env, feat_dim=20)
+    assert plan.info.safe_envelope_bytes > plan.info.envelope_bytes
+    assert plan.info.workspace_bytes == plan.info.envelope_bytes + plan.info.safe_envelope_bytes + plan.info.scratch_bytes
+    plan.bind_features(feat.cuda())
+    assert plan.step_status() == (0, 0)
+    # the batch that fits: exact on the tight plan, status clean
+    plan.step(torch.as_tensor(seeds[small]).cuda(), 900 + small)
+    res = plan.read_step()
+    compare_blocks(res, refs[small], "tight plan, fitting batch")
+    assert plan.step_status() == (1, 0)
+    # the batch that does not fit: flagged in pinned host memory, replayed on the twin, exact there
+    plan.step(torch.as_tensor(seeds[big]).cuda(), 900 + big)
+    torch.cuda.synchronize()
+    done, flags = plan.step_status()
+    assert done == 2 and flags == zg.FLAG_HOP_OVERFLOW(1)
+    plan.step_safe(torch.as_tensor(seeds[big]).cuda(), 900 + big)
+    twin = plan.safe_view()
+    res_safe = twin.read_step()
+    compare_blocks(res_safe, refs[big], "twin")
+    compare_features(oracle, res_safe, refs[big], feat.numpy(), "twin")
+    # the shared scratch is clean again: the tight plan keeps working
+    plan.overflow_clear()
+    plan.step(torch.as_tensor(seeds[small]).cuda(), 900 + small)
+    res = plan.read_step()
+    compare_blocks(res, refs[small], "tight plan after the fallback")
+    assert plan.step_status() == (3, 0)
+    # a plan without a twin refuses
+    plain = zg.Plan(dg, (8, 6), 300, zg.make_envelope(zg.ENV_MAX))
+    with pytest.raises(zg.ZgError) as ei:
+        plain.step_safe(torch.as_tensor(seeds0).cuda(), 1)
+    assert ei.value.status == zg.ESTATE

@@ -157,3 +157,15 @@ def test_oracle_sizes_stay_inside_max_envelope_and_near_model(oracle):
         for h in range(2):
             assert b.E[h] <= info.edge_cap[h]
         assert b.n[2] < info.maxsg_nodes[2]  # shortfall + dedup keep it below the worst case
+
+
+def test_plan_query_with_safe_twin_adds_the_worst_case_outputs_and_shares_the_scratch():
+    g = _stats_graph()
+    tight = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MODEL), feat_dim=8)
+    worst = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MAX), feat_dim=8)
+    both = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MODEL, flags=zg.PLAN_SAFE_TWIN), feat_dim=8)
+    assert tight.safe_envelope_bytes == 0
+    assert both.envelope_bytes == tight.envelope_bytes and both.safe_envelope_bytes == worst.envelope_bytes
+    assert both.scratch_bytes == worst.scratch_bytes  # one scratch region, sized for the twin
+    assert both.workspace_bytes == tight.envelope_bytes + worst.envelope_bytes + worst.scratch_bytes
+    assert list(both.node_cap[:3]) == list(tight.node_cap[:3])
