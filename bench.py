@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--no-fused", action="store_true", help="skip the extra pass with ZG_PLAN_FUSED_INPUT plans")
     ap.add_argument("--pipeline", type=int, default=4,
                     help="independent plans replayed round-robin on their own streams (consecutive mini-batches do not "
                          "depend on each other); 1 = strictly one step after the other")
@@ -96,8 +97,8 @@ def main():
     dg = zg.Graph(g.offsets, g.indices)
     H = len(cfg.fanouts)
 
-    def make_plan(mode):
-        env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX)
+    def make_plan(mode, flags=0):
+        env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags)
         p = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
         p.bind_features(feat)
         return p
@@ -143,6 +144,23 @@ def main():
         plan = plans[0]
     ms_per_step = wall / K * 1e3
     value = K / wall
+
+    # extra (not the headline): the same steps with plans that materialise only the frontier's rows of X and
+    # aggregate straight from the feature table (what the first GraphSAGE layer needs)
+    fused = None
+    if not args.no_fused:
+        fplans = [make_plan(env_mode, zg.PLAN_FUSED_INPUT) for _ in range(max(1, args.pipeline))]
+        fstreams = [zg.new_stream() for _ in fplans]
+        torch.cuda.synchronize()
+        wf1 = run(fplans[:1], [cur])
+        wfp = run(fplans, fstreams) if len(fplans) > 1 else wf1
+        assert flags_of(fplans) == 0
+        fused = {"value": K / min(wf1, wfp), "single_stream_value": K / wf1, "envelope_bytes": int(fplans[0].info.envelope_bytes),
+                 "note": "ZG_PLAN_FUSED_INPUT: X holds the rows of D_{H-1} only, the mean reads its input rows from the table"}
+        log(f"[bench] fused input: one stream {K / wf1:.0f} steps/s; pipelined {K / wfp:.0f} steps/s")
+        for fp in fplans:
+            fp.close()
+        del fplans
 
     # realised sizes of the timed steps from the device-side log
     logrec = plan.view_log().cpu().numpy().astype(np.int64)
@@ -236,6 +254,7 @@ def main():
                    "pipeline": f"{pipeline} plan(s) on {pipeline} stream(s), steps issued round-robin",
                    "host_syncs_in_timed_region": 1},
         "single_stream": {"value": K / wall_single, "ms_per_step": wall_single / K * 1e3},
+        "fused_input": fused,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -52,6 +52,9 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
 /* zg_envelope.flags */
 #define ZG_PLAN_EAGER 1u   /* launch the step's kernels one by one instead of replaying a hipGraph */
 #define ZG_PLAN_REPLACE 2u /* sample with replacement (the setting of the paper's Lemma 1) */
+#define ZG_PLAN_FUSED_INPUT 8u /* X holds the rows of the frontier D_{H-1} only and the aggregation reads its input rows
+                                 straight from the feature table: what the first GraphSAGE layer consumes, [X_self | mean],
+                                 with the rows that only feed the mean never written out */
 #define ZG_PLAN_SAFE_TWIN 4u /* also provision the worst-case twin of the plan: the paper's "cached safe graph" (section 4.3) */
 
 /* bits of the sticky device status word (zg_overflow_flag) */
@@ -112,13 +115,14 @@ typedef struct {
     const int32_t *d_col[ZG_MAX_HOPS];     /* [edge_cap[h]] local ids: block h is (row_ptr, col), n_h x n_{h+1} */
     int64_t node_cap[ZG_MAX_HOPS + 1];
     int64_t edge_cap[ZG_MAX_HOPS];
-    const float *d_X;   /* [node_cap[H], ldx] gathered feature rows of S_{H-1} (NULL if feat_dim == 0) */
+    const float *d_X;   /* [x_row_cap, ldx] gathered feature rows of S_{H-1} (NULL if feat_dim == 0) */
     int64_t ldx;
     const float *d_agg; /* [node_cap[H-1], ld_agg] mean of block H-1 over X */
     int64_t ld_agg;
     const uint32_t *d_log; /* ring of ZG_LOG_STRIDE-word records, one per step: epoch, flags, n[0..H], E[0..H-1], n_exact[1..H] */
     int32_t log_capacity;  /* records in the ring; record of step e sits at (e % log_capacity) */
     const uint32_t *d_epoch; /* number of steps run on this plan */
+    int64_t x_row_cap;       /* rows of d_X: node_cap[H], or node_cap[H-1] with ZG_PLAN_FUSED_INPUT (rows i < n_{H-1} are valid) */
 } zg_outputs;
 
 const char *zg_strerror(int status);

@@ -564,7 +564,7 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
 struct RowArgs {
     const float *src;       // gather: feature table; aggregate: input rows
     float *dst;
-    const int32_t *S;       // gather: global ids
+    const int32_t *S;       // gather: global ids; aggregate: non-null = input rows are feat[S[col]] (read from the table)
     const int32_t *row_ptr; // aggregate
     const int32_t *col;     // aggregate
     const uint32_t *n_rows; // device address of the row count
@@ -653,7 +653,10 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
     const int32_t e_begin = s_rp[0];
     uint32_t e_count = (uint32_t)(s_rp[rows] - e_begin);
     if (e_count > a.rows * a.max_fanout) e_count = a.rows * a.max_fanout;
-    for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) s_col[t] = a.col[e_begin + t];
+    for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) { // input row of every edge, -1 = none
+        const uint32_t c = (uint32_t)a.col[e_begin + t];
+        s_col[t] = c < n_in ? (a.S ? a.S[c] : (int32_t)c) : -1;
+    }
     __syncthreads();
     const uint32_t total = rows * a.dimv;
     for (uint32_t e = threadIdx.x; e < total; e += kBlock) {
@@ -665,8 +668,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
         T acc = VecOf<VEC>::zero();
 #pragma unroll 4
         for (uint32_t j = 0; j < k; ++j) {
-            const uint32_t cj = (uint32_t)s_col[b + j];
-            if (cj < n_in) acc += *reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
+            const int32_t cj = s_col[b + j];
+            if (cj >= 0) acc += *reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
         }
         const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
         *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
@@ -799,9 +802,10 @@ FinishArgs finish_args(const zg_plan_t *p, bool present)
 
 // gather (optional) + relabel of the last hop (optional) in one launch
 int launch_gather(const zg_plan_t *p, bool with_gather, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out,
-                  bool with_relabel, hipStream_t st)
+                  bool with_relabel, hipStream_t st, bool frontier_only = false)
 {
     const int H = p->lay.num_hops;
+    const int hx = frontier_only ? H - 1 : H; // rows to copy: D_{H-1} only, or all of S_{H-1}
     RowArgs a;
     std::memset(&a, 0, sizeof(a));
     int vec = 1;
@@ -812,13 +816,13 @@ int launch_gather(const zg_plan_t *p, bool with_gather, const float *d_feat, int
         a.src = d_feat;
         a.dst = d_out;
         a.S = p->S();
-        a.n_rows = &p->drmb()->n[H];
+        a.n_rows = &p->drmb()->n[hx];
         a.ld_src = ld;
         a.ld_dst = ld_out;
         a.inv = t.inv;
         a.dimv = t.dimv;
         a.rows = t.rows;
-        a.blocks = (uint32_t)((p->lay.node_cap[H] + t.rows - 1) / t.rows);
+        a.blocks = (uint32_t)((p->lay.node_cap[hx] + t.rows - 1) / t.rows);
     }
     const RelabelArgs ra = relabel_args(p, H - 1, with_relabel);
     const unsigned grid = a.blocks + ra.blocks;
@@ -833,7 +837,7 @@ int launch_gather(const zg_plan_t *p, bool with_gather, const float *d_feat, int
 
 // aggregation (optional) + end-of-step clean-up (optional) in one launch
 int launch_aggregate(const zg_plan_t *p, bool with_agg, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
-                     int64_t ld_out, bool with_finish, hipStream_t st)
+                     int64_t ld_out, bool with_finish, hipStream_t st, bool from_table = false)
 {
     RowArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -845,6 +849,7 @@ int launch_aggregate(const zg_plan_t *p, bool with_agg, int hop, const float *d_
         vec = t.vec;
         a.src = d_in;
         a.dst = d_out;
+        a.S = from_table ? p->S() : nullptr;
         a.row_ptr = p->row_ptr(hop);
         a.col = p->col(hop);
         a.n_rows = &p->drmb()->n[hop];
@@ -944,8 +949,10 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         ZG_HIP(hipGetLastError());
     }
     const bool feats = p->d_feat && L.feat_dim > 0;
-    int rc = launch_gather(p, feats, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, true, st);
+    const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0;
+    int rc = launch_gather(p, feats, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, true, st, fused);
     if (rc != ZG_OK) return rc;
+    if (fused) return launch_aggregate(p, feats, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ldx, true, st, true);
     return launch_aggregate(p, feats, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, true, st);
 }
 
@@ -1102,6 +1109,7 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
     o->d_log = p->log();
     o->log_capacity = kLogCapacity;
     o->d_epoch = &p->drmb()->epoch;
+    o->x_row_cap = L.x_rows;
     return ZG_OK;
 }
 

@@ -179,6 +179,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     if (rc != ZG_OK) return rc;
 
     const int64_t ldx = feat_dim > 0 ? (int64_t)align_up((size_t)feat_dim, 4) : 0;
+    const bool fused = (env->flags & ZG_PLAN_FUSED_INPUT) != 0;
     auto envelope_bytes_for = [&](const int64_t *node_cap) -> int64_t {
         size_t b = align_up(sizeof(Drmb), kAlign) + kGuard + align_up((size_t)kLogCapacity * ZG_LOG_STRIDE * 4, kAlign) + kGuard;
         b += align_up((size_t)node_cap[num_hops] * 4, kAlign) + kGuard;
@@ -187,7 +188,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
             b += 2 * (align_up((size_t)node_cap[h] * fanouts[h] * 4, kAlign) + kGuard);
         }
         if (feat_dim > 0) {
-            b += align_up((size_t)node_cap[num_hops] * ldx * 4, kAlign) + kGuard;
+            b += align_up((size_t)node_cap[fused ? num_hops - 1 : num_hops] * ldx * 4, kAlign) + kGuard;
             b += align_up((size_t)node_cap[num_hops - 1] * ldx * 4, kAlign) + kGuard;
         }
         return (int64_t)b;
@@ -234,7 +235,8 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_col[h] = place((size_t)L.edge_cap[h] * 4);
     }
     if (feat_dim > 0) {
-        L.off_X = place((size_t)L.node_cap[num_hops] * ldx * 4);
+        L.x_rows = L.node_cap[fused ? num_hops - 1 : num_hops];
+        L.off_X = place((size_t)L.x_rows * ldx * 4);
         L.off_agg = place((size_t)L.node_cap[num_hops - 1] * ldx * 4);
     }
     L.envelope_end = off;
@@ -266,7 +268,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     pi.grid_compact = (int32_t)L.compact_tiles;
     if (feat_dim > 0) {
         RowTiling tg = gather_tiling(feat_dim, true), ta = aggregate_tiling(feat_dim, true);
-        pi.grid_gather = (int32_t)((L.node_cap[num_hops] + tg.rows - 1) / tg.rows);
+        pi.grid_gather = (int32_t)((L.x_rows + tg.rows - 1) / tg.rows);
         pi.grid_aggregate = (int32_t)((L.node_cap[num_hops - 1] + ta.rows - 1) / ta.rows);
     }
     if (info) *info = pi;

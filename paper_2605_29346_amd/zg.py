@@ -17,7 +17,7 @@ LOG_STRIDE = 32
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 I32, I64 = 0, 1
 GRAPH_VALIDATE = 1
-PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN = 1, 2, 4
+PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN, PLAN_FUSED_INPUT = 1, 2, 4, 8
 ENV_MAX, ENV_MODEL, ENV_EXPLICIT = 0, 1, 2
 FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
 
@@ -61,7 +61,7 @@ class Outputs(C.Structure):
                 ("d_col", C.c_void_p * MAX_HOPS),
                 ("node_cap", C.c_int64 * (MAX_HOPS + 1)), ("edge_cap", C.c_int64 * MAX_HOPS),
                 ("d_X", C.c_void_p), ("ldx", C.c_int64), ("d_agg", C.c_void_p), ("ld_agg", C.c_int64),
-                ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p)]
+                ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p), ("x_row_cap", C.c_int64)]
 
 
 _lib = None
@@ -348,7 +348,7 @@ class Plan:
     def view_X(self):
         import torch
         H = self.num_hops
-        return self._view(self.out.d_X, self.out.node_cap[H] * self.out.ldx, torch.float32).view(-1, self.out.ldx)
+        return self._view(self.out.d_X, self.out.x_row_cap * self.out.ldx, torch.float32).view(-1, self.out.ldx)
 
     def view_agg(self):
         import torch
@@ -382,7 +382,8 @@ class Plan:
             col.append(c[: E[h]].cpu().numpy())
         X = agg = None
         if with_features and self.feat_dim > 0 and self.features is not None:
-            X = self.view_X()[: n[H], : self.feat_dim].cpu().numpy()
+            x_rows = n[H - 1] if (self.env.flags & PLAN_FUSED_INPUT) else n[H]
+            X = self.view_X()[: x_rows, : self.feat_dim].cpu().numpy()
             agg = self.view_agg()[: n[H - 1], : self.feat_dim].cpu().numpy()
         return StepResult(n, E, nx, flags, S, rp, nb, col, X, agg)
 

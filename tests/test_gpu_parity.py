@@ -276,3 +276,28 @@ def test_safe_twin_fallback_reproduces_the_untruncated_step(oracle):
     with pytest.raises(zg.ZgError) as ei:
         plain.step_safe(torch.as_tensor(seeds0).cuda(), 1)
     assert ei.value.status == zg.ESTATE
+
+
+@pytest.mark.parametrize("dim", [24, 600, 7])
+def test_fused_input_only_materialises_the_frontier_rows(oracle, dim):
+    # X = rows of D_{H-1} only; the aggregation reads its input rows from the feature table: same numbers
+    g = W.rmat_graph(12_000, 260_000, 33)
+    og = to_host_graph(oracle, g)
+    feat = W.feature_table(12_000, dim, 6)
+    seeds = W.SeedPool(g, 200, 3).batch_for(4).numpy()
+    ref = og.sample_blocks(seeds, (9, 5), 4242)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    plain = zg.Plan(dg, (9, 5), 200, zg.make_envelope(zg.ENV_MAX), feat_dim=dim)
+    fused = zg.Plan(dg, (9, 5), 200, zg.make_envelope(zg.ENV_MAX, flags=zg.PLAN_FUSED_INPUT), feat_dim=dim)
+    assert fused.info.envelope_bytes < plain.info.envelope_bytes
+    assert fused.out.x_row_cap == fused.out.node_cap[1] and plain.out.x_row_cap == plain.out.node_cap[2]
+    fused.bind_features(feat.cuda())
+    for rep in range(2):
+        fused.step(torch.as_tensor(seeds).cuda(), 4242)
+        res = fused.read_step()
+        compare_blocks(res, ref, "fused")
+        X_ref = oracle.gather(feat.numpy(), ref.S)
+        assert res.X.shape[0] == ref.n[1]
+        assert np.array_equal(res.X.view(np.uint32), X_ref[: ref.n[1]].view(np.uint32))
+        agg_ref = oracle.aggregate_mean(ref.row_ptr[-1], ref.col[-1], X_ref)
+        assert agg_error(oracle, res.agg, agg_ref, ref.row_ptr[-1], ref.col[-1], X_ref) <= 1e-5
