@@ -25,6 +25,9 @@
  *    (The paper names the mini-batch side of a hop the source set V_s and the sampled side the
  *    destination set V_d.)
  *  - fanouts[h] applies at hop h (fanouts[0] to the seeds).
+ *  - Environment: ZG_MAX_TICKETS (default 512) bounds how many workgroups of one kernel take a tile id
+ *    from a shared atomic counter; tiles grow to stay below it.  A tuning knob read at plan time; results
+ *    do not depend on it.
  */
 #ifndef ZG_H
 #define ZG_H

@@ -2,6 +2,7 @@
 // (paper section 4.3, Lemma 1, appendix A) and the fixed buffer layout / launch caps of a plan.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <map>
@@ -180,6 +181,9 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
 
     const int64_t ldx = feat_dim > 0 ? (int64_t)align_up((size_t)feat_dim, 4) : 0;
     const bool fused = (env->flags & ZG_PLAN_FUSED_INPUT) != 0;
+    // tuning knob: upper bound on the tickets (workgroups taking a tile id from one atomic counter) per kernel
+    int64_t max_tickets = kMaxTickets;
+    if (const char *e = std::getenv("ZG_MAX_TICKETS")) max_tickets = std::max(1, std::atoi(e));
     auto envelope_bytes_for = [&](const int64_t *node_cap) -> int64_t {
         size_t b = align_up(sizeof(Drmb), kAlign) + kGuard + align_up((size_t)kLogCapacity * ZG_LOG_STRIDE * 4, kAlign) + kGuard;
         b += align_up((size_t)node_cap[num_hops] * 4, kAlign) + kGuard;
@@ -208,13 +212,13 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         // every tile takes a ticket from one device-wide counter, and same-address atomics serialise
         // (about 15 ns each on MI355X): large frontiers give a workgroup several consecutive tiles per ticket
         L.sample_tpt[h] = 1;
-        while (L.sample_tpt[h] < kSampleMaxTpt && L.sample_tiles[h] > (int64_t)kMaxTickets * L.sample_tpt[h]) L.sample_tpt[h] *= 2;
+        while (L.sample_tpt[h] < kSampleMaxTpt && L.sample_tiles[h] > max_tickets * L.sample_tpt[h]) L.sample_tpt[h] *= 2;
         L.sample_blocks[h] = (L.sample_tiles[h] + L.sample_tpt[h] - 1) / L.sample_tpt[h];
     }
     {
         const int64_t words = (V + 31) / 32;
         L.compact_sub = 1;
-        while (L.compact_sub < 16 && words > (int64_t)kMaxTickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
+        while (L.compact_sub < 16 && words > max_tickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
         const size_t tile_words = (size_t)kCompactSubWords * L.compact_sub;
         L.bitmap_words = (int64_t)align_up((size_t)words, tile_words);
         L.compact_tiles = L.bitmap_words / (int64_t)tile_words;

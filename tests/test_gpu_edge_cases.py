@@ -1,0 +1,106 @@
+"""GPU parity on the degenerate and extreme shapes of the method: no edges at all, a single seed, every
+vertex a seed, the maximum number of hops, fanout 64 on a six-figure degree, vertex counts that are not a
+multiple of 32, and every tile-size variant of the chained-scan kernels (forced through ZG_MAX_TICKETS)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_29346_amd import workloads as W
+from paper_2605_29346_amd import zg
+from gpu_util import compare_blocks, run_and_compare, to_host_graph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    zg.lib()
+
+
+def _csr(rows, n):
+    off = np.zeros(n + 1, dtype=np.int64)
+    for v, r in rows.items():
+        off[v + 1] = len(r)
+    off = np.cumsum(off)
+    idx = np.concatenate([np.asarray(sorted(rows[v]), dtype=np.int32) for v in sorted(rows)] or [np.zeros(0, np.int32)])
+    return W.Graph(n, torch.as_tensor(off), torch.as_tensor(idx.astype(np.int32)))
+
+
+def test_graph_without_edges(oracle):
+    n = 1000
+    g = W.Graph(n, torch.zeros(n + 1, dtype=torch.int32), torch.zeros(0, dtype=torch.int32))
+    feat = W.feature_table(n, 8, 1)
+    seeds = np.arange(5, 45, dtype=np.int32)
+    _, res, ref = run_and_compare(oracle, g, feat, seeds, (3, 3), 7)
+    assert res.n == [40, 40, 40] and res.E == [0, 0] and np.all(res.agg == 0)
+
+
+def test_single_seed_and_single_vertex(oracle):
+    g = W.rmat_graph(5000, 90_000, 2)
+    feat = W.feature_table(5000, 12, 1)
+    deg = np.diff(g.offsets.numpy())
+    run_and_compare(oracle, g, feat, np.array([int(np.argmax(deg))], dtype=np.int32), (5, 5, 5), 3)
+    run_and_compare(oracle, g, feat, np.array([int(np.argmin(deg))], dtype=np.int32), (5, 5, 5), 3)
+    one = W.Graph(1, torch.tensor([0, 1], dtype=torch.int32), torch.tensor([0], dtype=torch.int32))  # a self-loop
+    _, res, _ = run_and_compare(oracle, one, torch.ones(1, 4), np.array([0], dtype=np.int32), (2, 2), 1)
+    assert res.n == [1, 1, 1] and res.E == [1, 1] and np.all(res.col[0] == 0)
+
+
+@pytest.mark.parametrize("nodes", [31, 32, 33, 1023, 4097])
+def test_every_vertex_is_a_seed(oracle, nodes):
+    g = W.rmat_graph(nodes, nodes * 12, nodes)
+    feat = W.feature_table(nodes, 4, 1)
+    seeds = np.random.RandomState(nodes).permutation(nodes).astype(np.int32)
+    _, res, _ = run_and_compare(oracle, g, feat, seeds, (4, 2), 11)
+    assert res.n == [nodes, nodes, nodes]  # nothing new can be discovered
+
+
+def test_maximum_hops(oracle):
+    g = W.rmat_graph(20_000, 200_000, 5)
+    feat = W.feature_table(20_000, 8, 1)
+    seeds = W.SeedPool(g, 16, 1).batch_for(0).numpy()
+    _, res, _ = run_and_compare(oracle, g, feat, seeds, (2,) * 8, 13)
+    assert len(res.E) == 8
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    with pytest.raises(zg.ZgError):
+        zg.Plan(dg, (2,) * 9, 16)
+
+
+def test_fanout_64_on_a_huge_row(oracle):
+    # one vertex adjacent to 150k others, fanout 64 (the widest lane group) and fanout 63, with and without replacement
+    n = 200_000
+    rnd = np.random.RandomState(3)
+    hub_nb = np.sort(rnd.choice(n, 150_000, replace=False)).astype(np.int32)
+    rows = {0: hub_nb.tolist()}
+    for v in range(1, 400):
+        rows[v] = sorted(set(rnd.randint(0, n, size=rnd.randint(0, 130)).tolist()))
+    g = _csr(rows, n)
+    feat = W.feature_table(n, 4, 2)
+    seeds = np.arange(0, 300, dtype=np.int32)
+    for fan in ((64, 2), (63, 64)):
+        for key in (1, 2):
+            run_and_compare(oracle, g, feat, seeds, fan, key)
+        run_and_compare(oracle, g, feat, seeds, fan, 5, replace=True)
+
+
+@pytest.mark.parametrize("max_tickets", [1, 2, 4, 16, 64])
+def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
+    # tiny ticket budgets force several tiles per sampling ticket and 2..16 rounds per compaction tile
+    os.environ["ZG_MAX_TICKETS"] = str(max_tickets)
+    try:
+        g = W.rmat_graph(600_000, 3_000_000, 17)
+        feat = W.feature_table(600_000, 4, 2)
+        og = to_host_graph(oracle, g)
+        pool = W.SeedPool(g, 3000, 5)
+        plan = None
+        for s in range(2):
+            plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (6, 5, 3), 40 + s, plan=plan, og=og)
+        info = plan.info
+        assert info.grid_compact <= max(max_tickets, (600_000 // 32 + 16383) // 16384)
+        assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 8)))
+    finally:
+        del os.environ["ZG_MAX_TICKETS"]
