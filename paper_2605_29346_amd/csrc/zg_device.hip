@@ -564,17 +564,18 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
 struct RowArgs {
     const float *src;       // gather: feature table; aggregate: input rows
     float *dst;
-    const int32_t *S;       // gather: global ids; aggregate: non-null = input rows are feat[S[col]] (read from the table)
+    const int32_t *S;       // gather: global ids of the rows to copy
     const int32_t *row_ptr; // aggregate
-    const int32_t *col;     // aggregate
+    const int32_t *col;     // aggregate: per edge, the index of its input row (local ids, or global ids: see n_cols)
     const uint32_t *n_rows; // device address of the row count
-    const uint32_t *n_cols; // aggregate: device address of the number of valid input rows
+    const uint32_t *n_cols; // aggregate: device address of the number of valid input rows, or null if `col_limit` holds it
+    uint32_t col_limit;     // aggregate: number of valid input rows when n_cols is null (num_nodes for global ids)
     int64_t ld_src, ld_dst;
     uint64_t inv;
     uint32_t dimv;
     uint32_t rows;
     uint32_t max_fanout;
-    uint32_t blocks; // workgroups given to this role (the launch's first ones; 0: role absent)
+    uint32_t blocks; // workgroups given to this role (0: role absent)
 };
 
 template <int VEC> struct VecOf;
@@ -587,21 +588,15 @@ template <> struct VecOf<1> {
     static __device__ __forceinline__ float zero() { return 0.0f; }
 };
 
-// "Gather": X[i,:] = feat[S[i],:], sharing its launch with the edge relabel of the last hop (workgroups
-// >= a.blocks).  A gather workgroup copies `rows` consecutive output rows; lanes walk the rows as one flat
-// run of 16-byte pieces so that rows whose length is not a multiple of the wave width still fill every
-// lane, four loads in flight per lane before the stores.
+// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
+// as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
+// fill every lane, four loads in flight per lane before the stores.
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void k_gather(RowArgs a, RelabelArgs last)
+__device__ __forceinline__ void gather_block(const RowArgs &a, uint32_t block, int32_t *s_id)
 {
-    if (blockIdx.x >= a.blocks) {
-        relabel_block(last, blockIdx.x - a.blocks);
-        return;
-    }
     typedef typename VecOf<VEC>::type T;
-    __shared__ int32_t s_id[kBlock];
     const uint32_t n = *a.n_rows;
-    const uint32_t row0 = blockIdx.x * a.rows;
+    const uint32_t row0 = block * a.rows;
     if (row0 >= n) return;
     const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
     if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
@@ -628,24 +623,18 @@ __global__ __launch_bounds__(kBlock) void k_gather(RowArgs a, RelabelArgs last)
     }
 }
 
-// "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:], sharing its launch with the end-of-
-// step clean-up (workgroups >= a.blocks).  An aggregation workgroup owns `rows` output rows; their row_ptr
-// slice and column ids are staged in LDS, then each lane owns one (row, 16-byte column piece) pair at a
-// time and accumulates over the row's edges in fp32.
+// "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:].  A workgroup owns `rows` output
+// rows; their row_ptr slice and input-row indices are staged in LDS, then each lane owns one (row, 16-byte
+// column piece) pair at a time and accumulates over the row's edges in fp32, in edge order.
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
+__device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block, int32_t *s_mem)
 {
-    if (blockIdx.x >= a.blocks) {
-        finish_block(fin, blockIdx.x - a.blocks);
-        return;
-    }
     typedef typename VecOf<VEC>::type T;
-    extern __shared__ int32_t s_mem[];
     int32_t *s_rp = s_mem;               // [rows+1]
     int32_t *s_col = s_mem + a.rows + 1; // [rows * max_fanout]
     const uint32_t n = *a.n_rows;
-    const uint32_t n_in = *a.n_cols;
-    const uint32_t row0 = blockIdx.x * a.rows;
+    const uint32_t n_in = a.n_cols ? *a.n_cols : a.col_limit;
+    const uint32_t row0 = block * a.rows;
     if (row0 >= n) return;
     const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
     for (uint32_t t = threadIdx.x; t <= rows; t += kBlock) s_rp[t] = a.row_ptr[row0 + t];
@@ -655,7 +644,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
     if (e_count > a.rows * a.max_fanout) e_count = a.rows * a.max_fanout;
     for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) { // input row of every edge, -1 = none
         const uint32_t c = (uint32_t)a.col[e_begin + t];
-        s_col[t] = c < n_in ? (a.S ? a.S[c] : (int32_t)c) : -1;
+        s_col[t] = c < n_in ? (int32_t)c : -1;
     }
     __syncthreads();
     const uint32_t total = rows * a.dimv;
@@ -674,6 +663,29 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs a, FinishArgs fin)
         const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
         *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
     }
+}
+
+// The two bandwidth-bound launches of a step, each with a small companion role on its last workgroups:
+// {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  An absent role has zero
+// workgroups (the stand-alone entry points launch the big role alone).
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_gather(RowArgs gat, RelabelArgs last)
+{
+    extern __shared__ int32_t s_mem[];
+    if (blockIdx.x < gat.blocks)
+        gather_block<VEC>(gat, blockIdx.x, s_mem);
+    else
+        relabel_block(last, blockIdx.x - gat.blocks);
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs agg, FinishArgs fin)
+{
+    extern __shared__ int32_t s_mem[];
+    if (blockIdx.x < agg.blocks)
+        aggregate_block<VEC>(agg, blockIdx.x, s_mem);
+    else
+        finish_block(fin, blockIdx.x - agg.blocks);
 }
 
 __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
@@ -800,76 +812,73 @@ FinishArgs finish_args(const zg_plan_t *p, bool present)
     return fa;
 }
 
-// gather (optional) + relabel of the last hop (optional) in one launch
-int launch_gather(const zg_plan_t *p, bool with_gather, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out,
-                  bool with_relabel, hipStream_t st, bool frontier_only = false)
+RowArgs gather_args(const zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, int hop_rows,
+                    int *vec)
 {
-    const int H = p->lay.num_hops;
-    const int hx = frontier_only ? H - 1 : H; // rows to copy: D_{H-1} only, or all of S_{H-1}
     RowArgs a;
     std::memset(&a, 0, sizeof(a));
-    int vec = 1;
-    if (with_gather) {
-        const bool al = aligned16(d_feat, ld) && aligned16(d_out, ld_out);
-        const RowTiling t = gather_tiling(dim, al);
-        vec = t.vec;
-        a.src = d_feat;
-        a.dst = d_out;
-        a.S = p->S();
-        a.n_rows = &p->drmb()->n[hx];
-        a.ld_src = ld;
-        a.ld_dst = ld_out;
-        a.inv = t.inv;
-        a.dimv = t.dimv;
-        a.rows = t.rows;
-        a.blocks = (uint32_t)((p->lay.node_cap[hx] + t.rows - 1) / t.rows);
-    }
-    const RelabelArgs ra = relabel_args(p, H - 1, with_relabel);
-    const unsigned grid = a.blocks + ra.blocks;
+    const RowTiling t = gather_tiling(dim, *vec == 4);
+    *vec = t.vec;
+    a.src = d_feat;
+    a.dst = d_out;
+    a.S = p->S();
+    a.n_rows = &p->drmb()->n[hop_rows];
+    a.ld_src = ld;
+    a.ld_dst = ld_out;
+    a.inv = t.inv;
+    a.dimv = t.dimv;
+    a.rows = t.rows;
+    a.blocks = (uint32_t)((p->lay.node_cap[hop_rows] + t.rows - 1) / t.rows);
+    return a;
+}
+
+// input rows addressed by `col` (local ids, bounded by n[hop+1]) or, with by_gid, by nbr_gid (global ids into the table)
+RowArgs aggregate_args(const zg_plan_t *p, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
+                       bool by_gid, int *vec)
+{
+    RowArgs a;
+    std::memset(&a, 0, sizeof(a));
+    const RowTiling t = aggregate_tiling(dim, *vec == 4);
+    *vec = t.vec;
+    a.src = d_in;
+    a.dst = d_out;
+    a.row_ptr = p->row_ptr(hop);
+    a.col = by_gid ? p->nbr(hop) : p->col(hop);
+    a.n_rows = &p->drmb()->n[hop];
+    a.n_cols = by_gid ? nullptr : &p->drmb()->n[hop + 1];
+    a.col_limit = (uint32_t)p->graph->num_nodes;
+    a.ld_src = ld_in;
+    a.ld_dst = ld_out;
+    a.inv = t.inv;
+    a.dimv = t.dimv;
+    a.rows = t.rows;
+    a.max_fanout = (uint32_t)p->lay.fanout[hop];
+    a.blocks = (uint32_t)((p->lay.node_cap[hop] + t.rows - 1) / t.rows);
+    return a;
+}
+
+int launch_gather(int vec, const RowArgs &gat, const RelabelArgs &ra, hipStream_t st)
+{
+    const unsigned grid = gat.blocks + ra.blocks;
     if (grid == 0) return ZG_OK;
+    const size_t lds = (size_t)kBlock * 4;
     if (vec == 4)
-        hipLaunchKernelGGL(k_gather<4>, dim3(grid), dim3(kBlock), 0, st, a, ra);
+        hipLaunchKernelGGL(k_gather<4>, dim3(grid), dim3(kBlock), lds, st, gat, ra);
     else
-        hipLaunchKernelGGL(k_gather<1>, dim3(grid), dim3(kBlock), 0, st, a, ra);
+        hipLaunchKernelGGL(k_gather<1>, dim3(grid), dim3(kBlock), lds, st, gat, ra);
     ZG_HIP(hipGetLastError());
     return ZG_OK;
 }
 
-// aggregation (optional) + end-of-step clean-up (optional) in one launch
-int launch_aggregate(const zg_plan_t *p, bool with_agg, int hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
-                     int64_t ld_out, bool with_finish, hipStream_t st, bool from_table = false)
+int launch_aggregate(int vec, const RowArgs &agg, const FinishArgs &fa, hipStream_t st)
 {
-    RowArgs a;
-    std::memset(&a, 0, sizeof(a));
-    int vec = 1;
-    size_t lds = 0;
-    if (with_agg) {
-        const bool al = aligned16(d_in, ld_in) && aligned16(d_out, ld_out);
-        const RowTiling t = aggregate_tiling(dim, al);
-        vec = t.vec;
-        a.src = d_in;
-        a.dst = d_out;
-        a.S = from_table ? p->S() : nullptr;
-        a.row_ptr = p->row_ptr(hop);
-        a.col = p->col(hop);
-        a.n_rows = &p->drmb()->n[hop];
-        a.n_cols = &p->drmb()->n[hop + 1];
-        a.ld_src = ld_in;
-        a.ld_dst = ld_out;
-        a.inv = t.inv;
-        a.dimv = t.dimv;
-        a.rows = t.rows;
-        a.max_fanout = (uint32_t)p->lay.fanout[hop];
-        a.blocks = (uint32_t)((p->lay.node_cap[hop] + t.rows - 1) / t.rows);
-        lds = ((size_t)t.rows + 1 + (size_t)t.rows * a.max_fanout) * 4;
-    }
-    const FinishArgs fa = finish_args(p, with_finish);
-    const unsigned grid = a.blocks + fa.blocks;
+    const unsigned grid = agg.blocks + fa.blocks;
     if (grid == 0) return ZG_OK;
+    const size_t lds = agg.blocks ? ((size_t)agg.rows + 1 + (size_t)agg.rows * agg.max_fanout) * 4 : 0;
     if (vec == 4)
-        hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, a, fa);
+        hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, agg, fa);
     else
-        hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, a, fa);
+        hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, agg, fa);
     ZG_HIP(hipGetLastError());
     return ZG_OK;
 }
@@ -948,12 +957,30 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         }
         ZG_HIP(hipGetLastError());
     }
+    // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all
+    // four roles, the mean reading its rows from the table, was measured: no gain - the two big roles are bound
+    // by the same memory fabric.)
     const bool feats = p->d_feat && L.feat_dim > 0;
     const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0;
-    int rc = launch_gather(p, feats, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, true, st, fused);
+    RowArgs agg, gat;
+    std::memset(&agg, 0, sizeof(agg));
+    std::memset(&gat, 0, sizeof(gat));
+    int vec = 1;
+    if (feats) {
+        vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ldx) && aligned16(p->agg(), L.ldx) ? 4 : 1;
+        int v1 = vec, v2 = vec;
+        // ZG_PLAN_FUSED_INPUT: X stops at the frontier's rows, so the mean takes its input rows from the table,
+        // addressed by the sampled global ids (feat[nbr_gid[e]] is the row X[col[e]] would have held)
+        if (fused)
+            agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ldx, true, &v1);
+        else
+            agg = aggregate_args(p, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, false, &v1);
+        gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, fused ? H - 1 : H, &v2);
+        vec = v1; // both tilings take the same vector width for the same dim and alignment
+    }
+    int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true), st);
     if (rc != ZG_OK) return rc;
-    if (fused) return launch_aggregate(p, feats, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ldx, true, st, true);
-    return launch_aggregate(p, feats, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, true, st);
+    return launch_aggregate(vec, agg, finish_args(p, true), st);
 }
 
 void drop_graph(zg_plan_t *p)
@@ -1168,7 +1195,9 @@ int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float 
 {
     if (!p || !d_feat || !d_out) return fail(ZG_EINVAL, "null argument");
     if (dim < 1 || dim > 32768 || ld < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
-    return launch_gather(p, true, d_feat, ld, dim, d_out, ld_out, false, static_cast<hipStream_t>(stream));
+    int vec = aligned16(d_feat, ld) && aligned16(d_out, ld_out) ? 4 : 1;
+    const RowArgs gat = gather_args(p, d_feat, ld, dim, d_out, ld_out, p->lay.num_hops, &vec);
+    return launch_gather(vec, gat, relabel_args(p, 0, false), static_cast<hipStream_t>(stream));
 }
 
 int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out, int64_t ld_out,
@@ -1177,7 +1206,9 @@ int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_i
     if (!p || !d_in || !d_out) return fail(ZG_EINVAL, "null argument");
     if (hop < 0 || hop >= p->lay.num_hops) return fail(ZG_EINVAL, "hop out of range");
     if (dim < 1 || dim > 32768 || ld_in < dim || ld_out < dim) return fail(ZG_EINVAL, "dim outside 1..32768 or a row stride < dim");
-    return launch_aggregate(p, true, hop, d_in, ld_in, dim, d_out, ld_out, false, static_cast<hipStream_t>(stream));
+    int vec = aligned16(d_in, ld_in) && aligned16(d_out, ld_out) ? 4 : 1;
+    const RowArgs agg = aggregate_args(p, hop, d_in, ld_in, dim, d_out, ld_out, false, &vec);
+    return launch_aggregate(vec, agg, finish_args(p, false), static_cast<hipStream_t>(stream));
 }
 
 int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag)

@@ -132,10 +132,8 @@ def main() -> None:
 
     if len(ingest) > args.skip_steps + 1:
         first = ingest[args.skip_steps]
-        # steady-state window: from the first timed step's ingest to the last step-ending kernel
-        step_end = max(i for i, r in enumerate(ours) if any(t in r["Kernel_Name"] for t in ("k_finish", "k_tail", "k_aggregate")) and i >= ingest[-1])
-        # stand-alone kernel launches after the last step are not part of the loop: stop at the first
-        # kernel that follows the last ingest's step
+        # steady-state window: from the first timed step's ingest to the end of the last step (stand-alone
+        # kernel launches after the last step are not part of the loop)
         last = ingest[-1]
         per_step = (ingest[-1] - first) // (len(ingest) - 1 - args.skip_steps)
         seg = ours[first: last + per_step]
