@@ -15,7 +15,7 @@ constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts o
 constexpr int kSampleBlock = 1024;      // threads per sampling workgroup: (1024 / G) frontier vertices x G slots
 constexpr int kCompactSubWords = 1024;  // bitmap words a compaction workgroup takes per round (one uint4 per thread)
 constexpr int kMaxTickets = 512;        // tiles are sized so that a kernel's ticket counter sees about this many atomics
-constexpr int kSampleMaxTpt = 8;        // most consecutive tiles a sampling workgroup takes per ticket
+constexpr int kSampleMaxTpt = 4;        // most consecutive tiles a sampling workgroup takes per ticket
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
 constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup (any workgroup size)

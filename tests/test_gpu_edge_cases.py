@@ -101,6 +101,6 @@ def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
             plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (6, 5, 3), 40 + s, plan=plan, og=og)
         info = plan.info
         assert info.grid_compact <= max(max_tickets, (600_000 // 32 + 16383) // 16384)
-        assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 8)))
+        assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 4)))  # at most 4 tiles of 256 vertices per ticket
     finally:
         del os.environ["ZG_MAX_TICKETS"]
