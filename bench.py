@@ -239,7 +239,14 @@ def main():
                 list(ex.map(one, chunk))
                 done += len(chunk)
         t_cpu = time.perf_counter() - t_cpu0
+        t1 = time.perf_counter()
+        n1 = 0
+        while n1 < min(K, 8) and time.perf_counter() - t1 < 5.0:
+            one(n1)
+            n1 += 1
+        single = n1 / (time.perf_counter() - t1)
         cpu = {"value": done / t_cpu, "unit": "mini-batches/s", "cores": min(cores, done), "kind": "oracle",
+               "single_thread_value": single,
                "sample": f"first {done} of the {K} timed steps of {cfg.name}, {cores} threads over independent steps, "
                          f"{t_cpu:.1f}s"}
 

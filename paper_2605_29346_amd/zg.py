@@ -176,6 +176,27 @@ def _stream_ptr(stream) -> int:
     return stream.cuda_stream
 
 
+def pilot_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, seed_batches, keys, *, margin: float = 0.20,
+                   flags: int = 0) -> Envelope:
+    """Plan-time pilot (the paper's warm-up iterations): run the given mini-batches once on a worst-case plan,
+    take the largest realised n_h per hop and return an explicit envelope with `margin` head-room over it.
+    Every step runs in the library; this only reads the realised sizes back."""
+    import torch
+    H = len(fanouts)
+    plan = Plan(graph, fanouts, batch, make_envelope(ENV_MAX, flags=flags & PLAN_REPLACE))
+    largest = [0] * (H + 1)
+    try:
+        for seeds, key in zip(seed_batches, keys):
+            plan.step(seeds, key)
+            torch.cuda.synchronize()
+            n = plan.view_counts()[0].cpu().tolist()
+            largest = [max(a, int(b)) for a, b in zip(largest, n)]
+    finally:
+        plan.close()
+    caps = [0] + [int(x * (1.0 + margin)) + 1 for x in largest[1:]]
+    return make_envelope(ENV_EXPLICIT, flags=flags, node_caps=caps)
+
+
 class Graph:
     """CSR graph on the device (torch tensors: int32/int64 offsets, int32 indices), borrowed by the library."""
 

@@ -301,3 +301,21 @@ def test_fused_input_only_materialises_the_frontier_rows(oracle, dim):
         assert np.array_equal(res.X.view(np.uint32), X_ref[: ref.n[1]].view(np.uint32))
         agg_ref = oracle.aggregate_mean(ref.row_ptr[-1], ref.col[-1], X_ref)
         assert agg_error(oracle, res.agg, agg_ref, ref.row_ptr[-1], ref.col[-1], X_ref) <= 1e-5
+
+
+def test_pilot_envelope_is_tight_and_does_not_overflow(oracle):
+    g = W.rmat_graph(50_000, 1_000_000, 12)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    pool = W.SeedPool(g, 400, 8)
+    batches = [pool.batch_for(s).cuda() for s in range(30)]
+    env = zg.pilot_envelope(dg, (10, 5), 400, batches[:8], range(100, 108), margin=0.2)
+    worst = dg.plan_query((10, 5), 400, zg.make_envelope(zg.ENV_MAX))
+    plan = zg.Plan(dg, (10, 5), 400, env)
+    assert plan.info.node_cap[2] < worst.node_cap[2] and plan.info.envelope_bytes < worst.envelope_bytes
+    for s, b in enumerate(batches):
+        plan.step(b, 100 + s)
+    torch.cuda.synchronize()
+    done, flags = plan.step_status()
+    assert done == 30 and int(plan.view_counts()[3].cpu()[0]) == 0  # 20 % head-room over 8 pilot steps held for 30
+    og = to_host_graph(oracle, g)
+    compare_blocks(plan.read_step(with_features=False), og.sample_blocks(batches[-1].cpu().numpy(), (10, 5), 129), "pilot plan")
