@@ -111,8 +111,11 @@ def main():
         t_start = time.perf_counter()
         for s in range(Wm, Wm + K):
             plans[s % P].step(batches[s], keys[s], streams[s % P])
+        t_issued = time.perf_counter() - t_start
         torch.cuda.synchronize()
-        return time.perf_counter() - t_start
+        t_all = time.perf_counter() - t_start
+        log(f"[bench] {P} stream(s): host issued {K} steps in {t_issued * 1e3:.2f} ms, device finished after {t_all * 1e3:.2f} ms")
+        return t_all
 
     def flags_of(plans):
         f = 0

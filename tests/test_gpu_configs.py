@@ -77,17 +77,17 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
 
 def test_medium_dense_full_size(oracle):
     cfg = W.CONFIGS["medium_dense"]
-    _run_config(oracle, cfg, steps=20, full_steps={0, 7, 19})
+    _run_config(oracle, cfg, steps=120, full_steps={0, 57, 119})
 
 
 def test_large_sparse_full_size(oracle):
     cfg = W.CONFIGS["large_sparse"]
-    _run_config(oracle, cfg, steps=20, full_steps={0, 13})
+    _run_config(oracle, cfg, steps=60, full_steps={0, 33})
 
 
 def test_envelope_stress_full_size(oracle):
     cfg = W.CONFIGS["envelope_stress"]
-    _run_config(oracle, cfg, steps=12, full_steps={0, 5})
+    _run_config(oracle, cfg, steps=60, full_steps={0, 41})
 
 
 @pytest.mark.skipif(os.environ.get("ZG_SKIP_VERY_LARGE") == "1", reason="ZG_SKIP_VERY_LARGE=1")
