@@ -319,3 +319,38 @@ def test_pilot_envelope_is_tight_and_does_not_overflow(oracle):
     assert done == 30 and int(plan.view_counts()[3].cpu()[0]) == 0  # 20 % head-room over 8 pilot steps held for 30
     og = to_host_graph(oracle, g)
     compare_blocks(plan.read_step(with_features=False), og.sample_blocks(batches[-1].cpu().numpy(), (10, 5), 129), "pilot plan")
+
+
+def test_plans_in_flight_on_separate_streams(oracle):
+    # consecutive mini-batches are independent: four plans over one graph, steps issued round-robin on four
+    # streams of their own with no sync in between; every step of every plan must match the checker
+    g = W.rmat_graph(60_000, 1_500_000, 31)
+    og = to_host_graph(oracle, g)
+    feat = W.feature_table(60_000, 48, 5)
+    feat_d = feat.cuda()
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    pool = W.SeedPool(g, 512, 6)
+    P, steps = 4, 40
+    plans, streams = [], []
+    for _ in range(P):
+        p = zg.Plan(dg, (10, 6), 512, zg.make_envelope(zg.ENV_MODEL), feat_dim=48)
+        p.bind_features(feat_d)
+        plans.append(p)
+        streams.append(zg.new_stream())
+    batches = [pool.batch_for(s).cuda() for s in range(steps)]
+    torch.cuda.synchronize()
+    for s in range(steps):
+        plans[s % P].step(batches[s], 3000 + s, streams[s % P])
+    torch.cuda.synchronize()
+    refs = [og.sample_blocks(batches[s].cpu().numpy(), (10, 6), 3000 + s) for s in range(steps)]
+    for q, p in enumerate(plans):
+        log = p.view_log().cpu().numpy()
+        assert p.step_status() == (steps // P, 0)
+        for i in range(steps // P):
+            ref = refs[i * P + q]
+            assert log[i][0] == i and log[i][1] == 0
+            assert list(log[i][2:5]) == ref.n and list(log[i][5:7]) == ref.E
+        last = refs[(steps // P - 1) * P + q]
+        res = p.read_step()
+        compare_blocks(res, last, f"plan {q}")
+        compare_features(oracle, res, last, feat.numpy(), f"plan {q}")
