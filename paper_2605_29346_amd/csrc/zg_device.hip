@@ -421,6 +421,15 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, Relab
     }
 }
 
+// Hop h, "compact / rank": the hop's bitmap holds exactly the new vertices (ids already in D_h never reach
+// it).  One chained pass over its |V|/32 words: the rank of a set bit is n_h + (set bits before it), so the
+// new vertices land behind D_h in ascending global id and get their local id at once.  Consumed words are
+// cleared for the next hop and their bits join "seen".  Entries beyond the cap are dropped (never written,
+// local id -1, not "seen") and the hop's overflow bit is raised.
+// A tile is 1024 * `rounds` words; each lane owns 4 * rounds consecutive words.  First the lanes count their set
+// bits, the counts are scanned inside the workgroup and the tile's total is chained to the predecessor tiles;
+// then every lane walks its words again (they come back from the cache) and expands its set bits.  Nothing is
+// kept in registers between the two walks, so the planner can trade tiles for tickets on the shared counter.
 struct CompactArgs {
     Drmb *drmb;
     uint32_t *bitmap;
@@ -429,50 +438,40 @@ struct CompactArgs {
     int32_t *local_id;
     uint64_t *status;
     uint32_t cap_next;
+    uint32_t rounds;
     int32_t hop;
     int32_t last_hop; // nothing is sampled from the vertices this hop adds: their "seen" bits are not needed
 };
 
-// Hop h, "compact / rank": the hop's bitmap holds exactly the new vertices (ids already in D_h never reach
-// it).  One chained pass over its |V|/32 words: the rank of a set bit is n_h + (set bits before it), so the
-// new vertices land behind D_h in ascending global id and get their local id at once.  Consumed words are
-// cleared for the next hop and their bits join "seen".  Entries beyond the cap are dropped (never written,
-// local id -1, not "seen") and the hop's overflow bit is raised.  A tile is SUB rounds of 1024 words held in
-// registers, SUB chosen by the planner so that the ticket counter sees a few hundred atomics at most.
-template <int SUB>
 __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 {
     __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[SUB][4];
+    __shared__ uint32_t s_wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
     __syncthreads();
     const uint32_t tile = s_tile;
-    // the tile = SUB rounds of 1024 words; in round s lane `tid` holds words [4 tid, 4 tid + 4) of the round
-    const size_t q0 = (size_t)tile * (SUB * kCompactSubWords / 4) + tid;
-    uint4 m[SUB];
-    uint32_t cnt[SUB], incl[SUB];
-#pragma unroll
-    for (int s = 0; s < SUB; ++s) m[s] = reinterpret_cast<const uint4 *>(a.bitmap)[q0 + (size_t)s * kBlock];
-#pragma unroll
-    for (int s = 0; s < SUB; ++s) {
-        cnt[s] = __popc(m[s].x) + __popc(m[s].y) + __popc(m[s].z) + __popc(m[s].w);
-        incl[s] = wave_incl_scan(cnt[s], lane);
-        if (lane == 63) s_wsum[s][wave] = incl[s];
+    // lane `tid` owns `rounds` consecutive uint4 (4 * rounds words) of the tile, so ranks inside the tile follow
+    // (lane, word) order and one workgroup scan of the lanes' counts is enough however large the tile is
+    const size_t q0 = ((size_t)tile * kBlock + tid) * a.rounds;
+    const uint4 *bm = reinterpret_cast<const uint4 *>(a.bitmap);
+
+    // ---- walk 1: this lane's count
+    uint32_t cnt = 0;
+#pragma unroll 8
+    for (uint32_t r = 0; r < a.rounds; ++r) {
+        const uint4 m = bm[q0 + r];
+        cnt += __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
     }
+    const uint32_t incl = wave_incl_scan(cnt, lane);
+    if (lane == 63) s_wsum[wave] = incl;
     __syncthreads();
-    uint32_t total = 0, my_off[SUB];
+    uint32_t wbase = 0, total = 0;
 #pragma unroll
-    for (int s = 0; s < SUB; ++s) {
-        uint32_t wb = 0, st = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave) wb += s_wsum[s][w];
-            st += s_wsum[s][w];
-        }
-        my_off[s] = total + wb + incl[s] - cnt[s];
-        total += st;
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) wbase += s_wsum[w];
+        total += s_wsum[w];
     }
     if (wave == 0) {
         const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
@@ -481,37 +480,41 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     __syncthreads();
     const uint32_t n_h = d->n[a.hop];
     const uint32_t base = n_h + s_base;
+
+    // ---- walk 2: ranks and expansion over this lane's words (they come back from the cache)
+    if (cnt) {
+        uint32_t rk = base + wbase + incl - cnt;
+        for (uint32_t r = 0; r < a.rounds; ++r) {
+            const size_t q = q0 + r;
+            const uint4 m = bm[q];
+            if ((m.x | m.y | m.z | m.w) == 0) continue;
+            const uint32_t word0 = (uint32_t)q * 4u;
+            const uint32_t nw[4] = {m.x, m.y, m.z, m.w};
+            uint32_t kept[4];
 #pragma unroll
-    for (int s = 0; s < SUB; ++s) {
-        if (cnt[s] == 0) continue;
-        const size_t q = q0 + (size_t)s * kBlock;
-        uint32_t r = base + my_off[s];
-        const uint32_t word0 = (uint32_t)q * 4u;
-        const uint32_t nw[4] = {m[s].x, m[s].y, m[s].z, m[s].w};
-        uint32_t kept[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint32_t bits = nw[c];
-            kept[c] = 0;
-            while (bits) {
-                const int b = __ffs((int)bits) - 1;
-                bits &= bits - 1;
-                const int32_t gid = (int32_t)(((word0 + c) << 5) + b);
-                if (r < a.cap_next) {
-                    a.S[r] = gid;
-                    a.local_id[gid] = (int32_t)r;
-                    kept[c] |= 1u << b;
-                } else {
-                    a.local_id[gid] = -1;
+            for (int c = 0; c < 4; ++c) {
+                uint32_t bits = nw[c];
+                kept[c] = 0;
+                while (bits) {
+                    const int b = __ffs((int)bits) - 1;
+                    bits &= bits - 1;
+                    const int32_t gid = (int32_t)(((word0 + c) << 5) + b);
+                    if (rk < a.cap_next) {
+                        a.S[rk] = gid;
+                        a.local_id[gid] = (int32_t)rk;
+                        kept[c] |= 1u << b;
+                    } else {
+                        a.local_id[gid] = -1;
+                    }
+                    ++rk;
                 }
-                ++r;
             }
+            if (!a.last_hop) { // this lane is the only writer of these words during the kernel
+                const uint4 sn = reinterpret_cast<const uint4 *>(a.seen)[q];
+                reinterpret_cast<uint4 *>(a.seen)[q] = make_uint4(sn.x | kept[0], sn.y | kept[1], sn.z | kept[2], sn.w | kept[3]);
+            }
+            reinterpret_cast<uint4 *>(a.bitmap)[q] = make_uint4(0, 0, 0, 0);
         }
-        if (!a.last_hop) { // this lane is the only writer of these words during the kernel
-            const uint4 sn = reinterpret_cast<const uint4 *>(a.seen)[q];
-            reinterpret_cast<uint4 *>(a.seen)[q] = make_uint4(sn.x | kept[0], sn.y | kept[1], sn.z | kept[2], sn.w | kept[3]);
-        }
-        reinterpret_cast<uint4 *>(a.bitmap)[q] = make_uint4(0, 0, 0, 0);
     }
     if (tile == gridDim.x - 1 && tid == 0) {
         const uint32_t exact = base + total;
@@ -947,14 +950,8 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         ca.cap_next = (uint32_t)L.node_cap[h + 1];
         ca.hop = h;
         ca.last_hop = h == H - 1 ? 1 : 0;
-        const dim3 gc((unsigned)L.compact_tiles);
-        switch (L.compact_sub) {
-        case 1: hipLaunchKernelGGL(k_compact_hop<1>, gc, dim3(kBlock), 0, st, ca); break;
-        case 2: hipLaunchKernelGGL(k_compact_hop<2>, gc, dim3(kBlock), 0, st, ca); break;
-        case 4: hipLaunchKernelGGL(k_compact_hop<4>, gc, dim3(kBlock), 0, st, ca); break;
-        case 8: hipLaunchKernelGGL(k_compact_hop<8>, gc, dim3(kBlock), 0, st, ca); break;
-        default: hipLaunchKernelGGL(k_compact_hop<16>, gc, dim3(kBlock), 0, st, ca); break;
-        }
+        ca.rounds = (uint32_t)L.compact_sub;
+        hipLaunchKernelGGL(k_compact_hop, dim3((unsigned)L.compact_tiles), dim3(kBlock), 0, st, ca);
         ZG_HIP(hipGetLastError());
     }
     // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all

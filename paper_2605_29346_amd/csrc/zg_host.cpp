@@ -217,8 +217,10 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     }
     {
         const int64_t words = (V + 31) / 32;
+        // compaction tiles: 1024 words per round, rounds doubled until the tile count fits the ticket budget
+        // (measured at 110 M vertices: 256-512 tiles are best; fewer, larger tiles only lengthen each workgroup's walk)
         L.compact_sub = 1;
-        while (L.compact_sub < 16 && words > max_tickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
+        while (L.compact_sub < 4096 && words > max_tickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
         const size_t tile_words = (size_t)kCompactSubWords * L.compact_sub;
         L.bitmap_words = (int64_t)align_up((size_t)words, tile_words);
         L.compact_tiles = L.bitmap_words / (int64_t)tile_words;

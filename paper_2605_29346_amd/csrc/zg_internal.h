@@ -49,7 +49,7 @@ struct Layout {
     int64_t sample_tiles[ZG_MAX_HOPS] = {};   // tiles of 1024 / G frontier vertices
     int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..8)
     int64_t sample_blocks[ZG_MAX_HOPS] = {};  // sampling workgroups = ceil(tiles / tiles per ticket)
-    int32_t compact_sub = 1;                  // rounds of 1024 words per compaction tile (1, 2, 4, 8 or 16)
+    int32_t compact_sub = 1;                  // rounds of 1024 words per compaction tile (a power of two)
     int64_t compact_tiles = 0;
     // byte offsets into the workspace
     size_t off_drmb = 0, off_log = 0, off_S = 0;
