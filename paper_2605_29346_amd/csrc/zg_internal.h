@@ -18,6 +18,7 @@ constexpr int kMaxTickets = 512;        // tiles are sized so that a kernel's ti
 constexpr int kSampleMaxTpt = 4;        // most consecutive tiles a sampling workgroup takes per ticket
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
+constexpr uint64_t kGatherStreamBytes = 160ull << 20; // gathered matrices above this size are copied with non-temporal accesses
 constexpr int kRelabelPerBlock = 1024;  // edges per relabel workgroup (any workgroup size)
 constexpr int kMailboxSlots = 256;      // per-step inputs in flight between host and device
 constexpr int kLogCapacity = 1024;      // records in the device-side step log
