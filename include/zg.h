@@ -128,6 +128,8 @@ typedef struct {
     int64_t x_row_cap;       /* rows of d_X: node_cap[H], or node_cap[H-1] with ZG_PLAN_FUSED_INPUT (rows i < n_{H-1} are valid) */
 } zg_outputs;
 
+/* Fixed text for a zg_status / thread-local detail of the calling thread's last failure.  Both return
+ * pointers owned by the library (the second one is valid until the thread's next failing call). */
 const char *zg_strerror(int status);
 const char *zg_last_error(void);
 
@@ -136,7 +138,10 @@ const char *zg_last_error(void);
  * choice).  d_offsets: [num_nodes+1] int32 or int64 (offsets_dtype); d_indices: [num_edges] int32;
  * num_nodes < 2^31, every degree < 2^31.  Both arrays are borrowed and must outlive the handle.
  * Synchronises (init time): the offsets are read back once to collect the degree statistics the
- * envelope model needs. */
+ * envelope model needs.  ZG_GRAPH_VALIDATE adds a device pass over the indices.
+ * Errors: ZG_EINVAL (null pointer, sizes out of range, offsets[0] != 0, offsets[num_nodes] != num_edges,
+ * offsets not monotone, validation found an id out of range or a row not strictly ascending), ZG_EHIP
+ * (read-back failed), ZG_ENOMEM (host).  *g is NULL on failure. */
 int zg_graph_create(zg_graph_t **g, int64_t num_nodes, int64_t num_edges, const void *d_offsets, int32_t offsets_dtype,
                     const int32_t *d_indices, uint32_t flags);
 /* A handle that carries degree statistics only (host arrays: distinct degree values and how many
@@ -144,6 +149,8 @@ int zg_graph_create(zg_graph_t **g, int64_t num_nodes, int64_t num_edges, const 
  * zg_plan rejects it. */
 int zg_graph_create_stats(zg_graph_t **g, int64_t num_nodes, int64_t num_edges, const int64_t *degrees,
                           const int64_t *counts, int64_t n_distinct);
+/* Releases the handle (NULL is fine); the device arrays stay the caller's.  Plans made from it must be
+ * destroyed first. */
 int zg_graph_destroy(zg_graph_t *g);
 /* Host pointers owned by the handle. */
 int zg_graph_degree_histogram(const zg_graph_t *g, int64_t *n_distinct, const int64_t **degrees, const int64_t **counts);
@@ -159,21 +166,32 @@ double zg_normal_quantile(double p);
 int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_distinct, const int32_t *fanouts,
                       int32_t num_hops, int32_t batch, int32_t with_replacement, double *mean, double *sigma);
 
-/* ---- plan -------------------------------------------------------------------------------------
+/* ---- plan (section 4.3: one-time provisioning of the execution envelope) ------------------------
  * Host only.  Caps, launch caps and workspace size for (fanouts, batch, envelope, feat_dim);
- * feat_dim = 0 plans the sampling/relabel/CSR part only.  1 <= fanouts[h] <= ZG_MAX_FANOUT. */
+ * feat_dim = 0 plans the sampling/relabel/CSR part only.  1 <= num_hops <= ZG_MAX_HOPS,
+ * 1 <= fanouts[h] <= ZG_MAX_FANOUT, 1 <= batch <= num_nodes, feat_dim <= 32768.
+ * Errors: ZG_EINVAL (any of those limits, unknown mode, a hop's edge capacity reaching 2^31),
+ * ZG_ESTATE (ZG_ENV_MODEL on a handle without degree statistics). */
 int zg_plan_query(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, const zg_envelope *env,
                   int32_t feat_dim, zg_plan_info *out);
-/* Lays the metadata buffer and every step buffer out at fixed addresses inside d_workspace (256-byte
- * aligned, >= workspace_bytes), initialises the scratch state on `stream` and builds the replayable
- * launch skeleton.  May synchronise.  The workspace belongs to the plan until zg_plan_destroy. */
+/* Sections 4.1-4.4: lays the device-resident metadata buffer and every step buffer out at fixed addresses
+ * inside d_workspace (device memory, 256-byte aligned, >= zg_plan_query's workspace_bytes), initialises the
+ * scratch state on `stream`, and captures the step - a fixed launch skeleton sized by the caps - into a
+ * hipGraph.  May synchronise.  The workspace belongs to the plan until zg_plan_destroy; the graph handle
+ * must outlive the plan; the current device must be the graph's.
+ * Errors: those of zg_plan_query, ZG_EINVAL (workspace null or misaligned), ZG_ENOMEM (workspace too small,
+ * pinned host memory), ZG_ESTATE (statistics-only graph handle, other device), ZG_EHIP.  *p is NULL on failure. */
 int zg_plan(zg_plan_t **p, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
             const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream);
 /* Waits for the device to go idle (a step in flight still uses the plan), then releases the plan. */
 int zg_plan_destroy(zg_plan_t *p);
-/* Makes gather + aggregation part of the step: d_feat is the [num_nodes, ld] fp32 table (row stride ld
- * elements, >= feat_dim), borrowed.  Rebuilds the captured graph; call between steps, may synchronise. */
+/* Makes gather + aggregation (section 2.2, "feature copy" and the first GraphSAGE aggregation) part of the
+ * step: d_feat is the [num_nodes, ld] fp32 table in device memory (row stride ld elements, >= feat_dim),
+ * borrowed until the plan is destroyed or another table is bound.  Rebuilds the captured graph: call it
+ * between steps (nothing of this plan in flight).  Errors: ZG_ESTATE (plan made with feat_dim = 0),
+ * ZG_EINVAL (null table, ld < feat_dim), ZG_EHIP. */
 int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld);
+/* Section 4.4, "stable buffers and inputs": the device addresses the step writes to.  Host only. */
 int zg_plan_outputs(const zg_plan_t *p, zg_outputs *out);
 
 /* ---- per step ---------------------------------------------------------------------------------
@@ -184,13 +202,20 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *out);
  * the device and never allocates; only when 255 earlier steps of this plan are still unfinished does
  * it wait, on the host, for the oldest one (a counter the device publishes in the same pinned ring).
  * Results are in the plan's output buffers once `stream` reaches this point.  Steps of one plan must be
- * stream-ordered one after another and issued from one host thread at a time. */
+ * stream-ordered one after another and issued from one host thread at a time.  Invalid seeds do not fault:
+ * they raise ZG_FLAG_SEED_* bits in the device status word and make the step's outputs undefined.
+ * Errors: ZG_EINVAL (null), ZG_ESTATE (no captured graph), ZG_EHIP (launch failed; nothing was enqueued). */
 int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
-/* Stand-alone feature gather for the plan's current S_{H-1}: d_out[i,:] = d_feat[S[i],:], i < n_H;
- * rows >= n_H of d_out are not written. */
+/* Stand-alone feature gather (section 2.2, "feature copy") for the vertex list the plan's last step left
+ * on the device: d_out[i,:] = d_feat[S[i],:], i < n_H (n_H is read on the device); rows >= n_H of d_out are
+ * not written.  d_feat: [num_nodes, ld], d_out: [>= n_H, ld_out], both fp32 device memory, 1 <= dim <= 32768.
+ * Enqueues one kernel on `stream`; never synchronises.  Errors: ZG_EINVAL, ZG_EHIP. */
 int zg_gather(zg_plan_t *p, const float *d_feat, int64_t ld, int32_t dim, float *d_out, int64_t ld_out, void *stream);
-/* Stand-alone mean aggregation on block `hop` of the current step: d_out[i,:] = mean of d_in[col[e],:]
- * over row i (0 for an empty row), i < n_hop. */
+/* Stand-alone GraphSAGE mean aggregation (section 2.2, "subgraph GNN training": the neighbor mean of a layer)
+ * on block `hop` of the plan's last step: d_out[i,:] = mean over e in row i of d_in[col[e],:] (0 for an empty
+ * row), i < n_hop; d_in: [>= n_{hop+1}, ld_in], d_out: [>= n_hop, ld_out], fp32 device memory.  Any hop works,
+ * so deeper layers can aggregate their own activations.  Accumulates in fp32 in edge order.  Enqueues one
+ * kernel on `stream`; never synchronises.  Errors: ZG_EINVAL (hop or dim out of range, strides), ZG_EHIP. */
 int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_in, int32_t dim, float *d_out,
                       int64_t ld_out, void *stream);
 /* Overflow-safe fallback (section 4.3): replays the same mini-batch on the plan's worst-case twin (needs
@@ -205,8 +230,10 @@ int zg_plan_outputs_safe(const zg_plan_t *p, zg_outputs *out);
  * of every step writes, so a caller that already knows step k has finished (its own event or sync) can
  * decide about the fallback without reading device memory. */
 int zg_step_status(const zg_plan_t *p, uint32_t *steps_completed, uint32_t *last_flags);
-/* Device address of the sticky status word (ZG_FLAG_*).  The caller reads it when it chooses. */
+/* Section 4.3, "overflow-safe fallback": device address of the plan's sticky status word (ZG_FLAG_* bits
+ * accumulate over steps).  The caller reads it when it chooses (async copy + event, end of an epoch).  Host only. */
 int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag);
+/* Clears the sticky word with a one-lane kernel on `stream` (no memset node: safe under graph capture). */
 int zg_overflow_clear(zg_plan_t *p, void *stream);
 
 #ifdef __cplusplus
