@@ -9,7 +9,7 @@ import torch
 
 from paper_2605_29346_amd import workloads as W
 from paper_2605_29346_amd import zg
-from gpu_util import compare_blocks, run_and_compare, to_host_graph
+from gpu_util import agg_error, compare_blocks, run_and_compare, to_host_graph
 
 pytestmark = pytest.mark.gpu
 
@@ -104,3 +104,48 @@ def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
         assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 4)))  # at most 4 tiles of 256 vertices per ticket
     finally:
         del os.environ["ZG_MAX_TICKETS"]
+
+
+def test_randomised_configurations(oracle):
+    # 40 random (graph, batch, hops, fanouts, feature width, envelope mode, replacement) draws, two steps each
+    rnd = np.random.RandomState(20260529)
+    for trial in range(40):
+        nodes = int(rnd.choice([50, 333, 2048, 7001, 40_000, 150_000]))
+        avg_deg = float(rnd.choice([0.5, 3, 20, 120]))
+        draws = max(64, int(nodes * avg_deg))
+        i64 = bool(rnd.randint(2))
+        g = W.rmat_graph(nodes, draws, 1000 + trial, offsets_dtype=torch.int64 if i64 else torch.int32)
+        H = int(rnd.randint(1, 5))
+        fan = tuple(int(rnd.choice([1, 2, 3, 5, 8, 13, 16, 25, 40, 64])) for _ in range(H))
+        batch = int(min(nodes, rnd.choice([1, 7, 64, 300, 1024])))
+        dim = int(rnd.choice([1, 4, 10, 32, 100, 257]))
+        replace = bool(rnd.randint(4) == 0)
+        mode = [zg.ENV_MAX, zg.ENV_MODEL][int(rnd.randint(2))]
+        feat = W.feature_table(nodes, dim, trial)
+        og = to_host_graph(oracle, g)
+        dg = zg.Graph(g.offsets.cuda(), g.indices.cuda(), validate=True)
+        flags = (zg.PLAN_REPLACE if replace else 0) | (zg.PLAN_FUSED_INPUT if rnd.randint(3) == 0 else 0)
+        try:
+            plan = zg.Plan(dg, fan, batch, zg.make_envelope(mode, flags=flags), feat_dim=dim)
+        except zg.ZgError as e:  # a hop's edge capacity reaching 2^31 is refused, nothing else may be
+            assert "2^31" in str(e), str(e)
+            continue
+        plan.bind_features(feat.cuda())
+        pool = W.SeedPool(g, batch, trial)
+        label = f"trial {trial}: V={nodes} draws={draws} i64={i64} fan={fan} B={batch} dim={dim} replace={replace} mode={mode} flags={flags}"
+        for s in range(2):
+            seeds = pool.batch_for(s).numpy()
+            plan.step(torch.as_tensor(seeds).cuda(), 77 + s)
+            res = plan.read_step()
+            ref = og.sample_blocks(seeds, fan, 77 + s, with_replacement=replace)
+            if res.flags:  # the model envelope may be too tight on these odd little graphs: then the twin-free contract is "flagged"
+                assert mode == zg.ENV_MODEL and (res.flags & 0xFF), label
+                plan.overflow_clear()
+                continue
+            compare_blocks(res, ref, label)
+            X_ref = oracle.gather(feat.numpy(), ref.S)
+            xr = ref.n[-2] if flags & zg.PLAN_FUSED_INPUT else ref.n[-1]
+            assert np.array_equal(res.X.view(np.uint32), X_ref[:xr].view(np.uint32)), label
+            agg_ref = oracle.aggregate_mean(ref.row_ptr[-1], ref.col[-1], X_ref)
+            assert agg_error(oracle, res.agg, agg_ref, ref.row_ptr[-1], ref.col[-1], X_ref) <= 1e-5, label
+        plan.close()
