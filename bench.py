@@ -165,6 +165,24 @@ def main():
             fp.close()
         del fplans
 
+    # extra: what the device-side fallback conditional costs when it never fires (the twin's gated kernels
+    # return at once; the plan itself is the same model envelope)
+    auto_fb = None
+    if not args.no_fused and env_mode == "model":
+        aplans = [make_plan(env_mode, zg.PLAN_AUTO_FALLBACK) for _ in range(max(1, args.pipeline))]
+        astreams = [zg.new_stream() for _ in aplans]
+        torch.cuda.synchronize()
+        wa1 = run(aplans[:1], [cur])
+        wap = run(aplans, astreams) if len(aplans) > 1 else wa1
+        fell = sum(int(p.safe_view().epoch()) for p in aplans)
+        auto_fb = {"value": K / min(wa1, wap), "single_stream_value": K / wa1, "fallbacks": fell,
+                   "safe_envelope_bytes": int(aplans[0].info.safe_envelope_bytes),
+                   "note": "ZG_PLAN_AUTO_FALLBACK: the worst-case twin's kernels ride in every step's graph behind a device-side gate"}
+        log(f"[bench] automatic fallback armed: one stream {K / wa1:.0f} steps/s; pipelined {K / wap:.0f} steps/s; fell back {fell} times")
+        for ap_ in aplans:
+            ap_.close()
+        del aplans
+
     # realised sizes of the timed steps from the device-side log
     logrec = plan.view_log().cpu().numpy().astype(np.int64)
     total_steps = plan.epoch()
@@ -265,6 +283,7 @@ def main():
                    "host_syncs_in_timed_region": 1},
         "single_stream": {"value": K / wall_single, "ms_per_step": wall_single / K * 1e3},
         "fused_input": fused,
+        "auto_fallback": auto_fb,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -59,6 +59,13 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
                                  straight from the feature table: what the first GraphSAGE layer consumes, [X_self | mean],
                                  with the rows that only feed the mean never written out */
 #define ZG_PLAN_SAFE_TWIN 4u /* also provision the worst-case twin of the plan: the paper's "cached safe graph" (section 4.3) */
+#define ZG_PLAN_AUTO_FALLBACK 16u /* (brings the twin) the step's captured graph also holds the twin's kernels, behind a
+                                 device-side conditional: every workgroup of theirs returns at once unless the plan's own
+                                 step raised a hop-overflow bit, in which case they redo the mini-batch on the worst-case
+                                 buffers before the graph ends.  The device word zg_outputs.d_active (of zg_plan_outputs)
+                                 then reads 1 and the step's valid outputs are those of zg_plan_outputs_safe; otherwise it
+                                 reads 0.  A consumer kernel selects its inputs by that word: the host never looks at a
+                                 flag.  zg_step_safe is refused on such a plan (ZG_ESTATE). */
 
 /* bits of the sticky device status word (zg_overflow_flag) */
 #define ZG_FLAG_HOP_OVERFLOW(h) (1u << (h)) /* |S_h| exceeded its cap at hop h: outputs of the step invalid */
@@ -126,6 +133,8 @@ typedef struct {
     int32_t log_capacity;  /* records in the ring; record of step e sits at (e % log_capacity) */
     const uint32_t *d_epoch; /* number of steps run on this plan */
     int64_t x_row_cap;       /* rows of d_X: node_cap[H], or node_cap[H-1] with ZG_PLAN_FUSED_INPUT (rows i < n_{H-1} are valid) */
+    const uint32_t *d_active; /* ZG_PLAN_AUTO_FALLBACK: 1 if the last step fell back to the twin (its outputs are the valid
+                                 ones), else 0; always 0 on other plans */
 } zg_outputs;
 
 /* Fixed text for a zg_status / thread-local detail of the calling thread's last failure.  Both return
@@ -222,7 +231,8 @@ int zg_aggregate_mean(zg_plan_t *p, int32_t hop, const float *d_in, int64_t ld_i
  * ZG_PLAN_SAFE_TWIN).  Same contract as zg_step; because the random draws are keyed by (key, hop, vertex,
  * slot), the twin produces exactly what the tight plan would have produced without the overflow.  Its
  * outputs live in the twin's own buffers (zg_plan_outputs_safe); the scratch state is shared, so the call
- * must be stream-ordered with the plan's other steps. */
+ * must be stream-ordered with the plan's other steps.  Errors: ZG_ESTATE (no twin, or the plan falls back
+ * by itself: ZG_PLAN_AUTO_FALLBACK), otherwise as zg_step. */
 int zg_step_safe(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
 int zg_plan_outputs_safe(const zg_plan_t *p, zg_outputs *out);
 /* Host only, no device call: how many steps of this plan have finished, and the ZG_FLAG_* bits the last

@@ -134,9 +134,20 @@ struct Mailbox {
     } slot[kMailboxSlots];
 };
 
+// Device-side conditional of the overflow-safe fallback (paper section 4.3): the worst-case twin's kernels sit
+// behind the plan's own in the same captured graph and every one of their workgroups returns at once unless
+// the plan's step raised a hop-overflow bit - a fixed launch skeleton whose surplus work exits early, like
+// the over-provisioned grids of section 4.2.  `gate` is the plan's metadata buffer (null: always run).
+constexpr uint32_t kHopOverflowMask = 0xFFFFu;
+__device__ __forceinline__ bool gate_closed(const Drmb *gate)
+{
+    return gate != nullptr && (gate->step_flags & kHopOverflowMask) == 0u;
+}
+
 struct IngestArgs {
     Drmb *drmb;
-    const Mailbox *mailbox;
+    const Drmb *gate;       // gated twin: the step's inputs are those of the gate owner's step that has just finished
+    const Mailbox *mailbox; // the mailbox the inputs are read from (the gate owner's when gated)
     int32_t *S;
     int32_t *local_id;
     uint32_t *seen;
@@ -152,10 +163,11 @@ struct IngestArgs {
 __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
 {
     __shared__ unsigned long long s_in[2];
+    if (gate_closed(a.gate)) return;
     const uint32_t gtid = blockIdx.x * kBlock + threadIdx.x;
     const uint32_t gsize = gridDim.x * kBlock;
     if (threadIdx.x == 0) { // one read of the host-resident slot per workgroup
-        const uint32_t slot = a.drmb->epoch % kMailboxSlots;
+        const uint32_t slot = (a.gate ? a.gate->epoch - 1u : a.drmb->epoch) % kMailboxSlots;
         s_in[0] = __hip_atomic_load(&a.mailbox->slot[slot].seeds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         s_in[1] = __hip_atomic_load(&a.mailbox->slot[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
@@ -192,6 +204,7 @@ __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
 
 struct RelabelArgs {
     const Drmb *drmb;
+    const Drmb *gate; // consulted by the gather launch (the sampling launch has its own)
     const int32_t *nbr;
     const int32_t *local_id;
     int32_t *col;
@@ -220,6 +233,7 @@ struct SampleArgs {
     const void *offsets;
     const int32_t *indices;
     Drmb *drmb;
+    const Drmb *gate;
     const int32_t *S;
     int32_t *row_ptr;
     int32_t *nbr;
@@ -256,6 +270,7 @@ struct SampleArgs {
 template <typename OffT>
 __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, RelabelArgs prev)
 {
+    if (gate_closed(a.gate)) return;
     if (blockIdx.x >= a.blocks) {
         relabel_block(prev, blockIdx.x - a.blocks);
         return;
@@ -432,6 +447,7 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, Relab
 // kept in registers between the two walks, so the planner can trade tiles for tickets on the shared counter.
 struct CompactArgs {
     Drmb *drmb;
+    const Drmb *gate;
     uint32_t *bitmap;
     uint32_t *seen;
     int32_t *S;
@@ -447,6 +463,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 {
     __shared__ uint32_t s_tile, s_base;
     __shared__ uint32_t s_wsum[4];
+    if (gate_closed(a.gate)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
     if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
@@ -529,6 +546,9 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
 
 struct FinishArgs {
     Drmb *drmb;
+    const Drmb *gate;       // gated twin: the plan whose step this launch ends
+    Mailbox *gate_mailbox;  // ... and its mailbox: the step counts as completed only now
+    int32_t defer_completed; // plan with a gated twin behind it: leave `completed` to the twin's last launch
     Mailbox *mailbox;
     const int32_t *S;
     uint32_t *seen;
@@ -540,6 +560,12 @@ struct FinishArgs {
 // End of step: the "seen" words of this step's frontier vertices (everything in D_{H-1}: the seeds and
 // what hops 0..H-2 added) go back to zero - the bitmaps over |V| are never cleared as a whole - and the
 // step is appended to the device-side log; the step counter advances.
+// last launch of a step that carries a gated twin: the owner's step is complete whether or not the twin ran
+__device__ __forceinline__ void publish_gate_owner(const FinishArgs &a)
+{
+    __hip_atomic_store(&a.gate_mailbox->completed, a.gate->epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block)
 {
     const uint32_t n = a.drmb->n[a.num_hops - 1];
@@ -559,8 +585,11 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         for (int h = 0; h < a.num_hops; ++h) rec[p++] = d->E[h];
         for (int h = 1; h <= a.num_hops; ++h) rec[p++] = d->n_exact[h];
         d->epoch = epoch + 1;
+        d->active = (d->step_flags & kHopOverflowMask) != 0u && a.defer_completed ? 1u : 0u;
         __hip_atomic_store(&a.mailbox->status[epoch % kMailboxSlots], d->step_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (!a.defer_completed)
+            __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (a.gate) publish_gate_owner(a);
     }
 }
 
@@ -696,6 +725,7 @@ template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_gather(RowArgs gat, RelabelArgs last)
 {
     extern __shared__ int32_t s_mem[];
+    if (gate_closed(last.gate)) return;
     if (blockIdx.x < gat.blocks)
         gather_block<VEC>(gat, blockIdx.x, s_mem);
     else
@@ -706,6 +736,10 @@ template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs agg, FinishArgs fin)
 {
     extern __shared__ int32_t s_mem[];
+    if (gate_closed(fin.gate)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) publish_gate_owner(fin);
+        return;
+    }
     if (blockIdx.x < agg.blocks)
         aggregate_block<VEC>(agg, blockIdx.x, s_mem);
     else
@@ -805,10 +839,11 @@ namespace {
 
 bool aligned16(const void *p, int64_t ld) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 4) == 0; }
 
-RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present)
+RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present, const zg_plan_t *gate = nullptr)
 {
     RelabelArgs ra;
     std::memset(&ra, 0, sizeof(ra));
+    ra.gate = gate ? gate->drmb() : nullptr;
     if (!present) return ra;
     ra.drmb = p->drmb();
     ra.nbr = p->nbr(hop);
@@ -820,13 +855,16 @@ RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present)
     return ra;
 }
 
-FinishArgs finish_args(const zg_plan_t *p, bool present)
+FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate = nullptr, bool defer_completed = false)
 {
     FinishArgs fa;
     std::memset(&fa, 0, sizeof(fa));
     if (!present) return fa;
     const int H = p->lay.num_hops;
     fa.drmb = p->drmb();
+    fa.gate = gate ? gate->drmb() : nullptr;
+    fa.gate_mailbox = gate ? gate->mailbox_dev : nullptr;
+    fa.defer_completed = defer_completed ? 1 : 0;
     fa.mailbox = p->mailbox_dev;
     fa.S = p->S();
     fa.seen = p->seen();
@@ -907,11 +945,12 @@ int launch_aggregate(int vec, const RowArgs &agg, const FinishArgs &fa, hipStrea
     return ZG_OK;
 }
 
-int launch_ingest(const zg_plan_t *p, hipStream_t st)
+int launch_ingest(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate)
 {
     IngestArgs a;
     a.drmb = p->drmb();
-    a.mailbox = p->mailbox_dev;
+    a.gate = gate ? gate->drmb() : nullptr;
+    a.mailbox = gate ? gate->mailbox_dev : p->mailbox_dev;
     a.S = p->S();
     a.local_id = p->local_id();
     a.seen = p->seen();
@@ -926,13 +965,15 @@ int launch_ingest(const zg_plan_t *p, hipStream_t st)
     return ZG_OK;
 }
 
-// a whole step, in order, on one stream (captured once, or issued eagerly)
-int enqueue_body(const zg_plan_t *p, hipStream_t st)
+// a whole step, in order, on one stream (captured once, or issued eagerly).  With `gate` the kernels are those
+// of gate's worst-case twin `p`, run on gate's inputs and only if gate's step overflowed; `defer_completed`
+// marks a plan whose gated twin follows in the same sequence.
+int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nullptr, bool defer_completed = false)
 {
     const Layout &L = p->lay;
     const zg_graph_t *g = p->graph;
     const int H = L.num_hops;
-    int rc0 = launch_ingest(p, st);
+    int rc0 = launch_ingest(p, st, gate);
     if (rc0 != ZG_OK) return rc0;
     for (int h = 0; h < H; ++h) {
         SampleArgs sa;
@@ -940,6 +981,7 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         sa.offsets = g->d_offsets;
         sa.indices = g->d_indices;
         sa.drmb = p->drmb();
+        sa.gate = gate ? gate->drmb() : nullptr;
         sa.S = p->S();
         sa.row_ptr = p->row_ptr(h);
         sa.nbr = p->nbr(h);
@@ -963,6 +1005,7 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
 
         CompactArgs ca;
         ca.drmb = p->drmb();
+        ca.gate = gate ? gate->drmb() : nullptr;
         ca.bitmap = p->bitmap();
         ca.seen = p->seen();
         ca.S = p->S();
@@ -996,9 +1039,18 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st)
         gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, fused ? H - 1 : H, &v2);
         vec = v1; // both tilings take the same vector width for the same dim and alignment
     }
-    int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true), st);
+    int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true, gate), st);
     if (rc != ZG_OK) return rc;
-    return launch_aggregate(vec, agg, finish_args(p, true), st);
+    return launch_aggregate(vec, agg, finish_args(p, true, gate, defer_completed), st);
+}
+
+// the plan's step, followed - with ZG_PLAN_AUTO_FALLBACK - by its twin's step behind the device-side gate
+int enqueue_step(const zg_plan_t *p, hipStream_t st)
+{
+    const bool autofb = (p->flags & ZG_PLAN_AUTO_FALLBACK) && p->twin;
+    int rc = enqueue_body(p, st, nullptr, autofb);
+    if (rc == ZG_OK && autofb) rc = enqueue_body(p->twin, st, p, false);
+    return rc;
 }
 
 void drop_graph(zg_plan_t *p)
@@ -1015,7 +1067,7 @@ int build_graph(zg_plan_t *p)
     if (p->flags & ZG_PLAN_EAGER) return ZG_OK;
     if (!p->capture_stream) ZG_HIP(hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking));
     ZG_HIP(hipStreamBeginCapture(p->capture_stream, hipStreamCaptureModeThreadLocal));
-    int rc = enqueue_body(p, p->capture_stream);
+    int rc = enqueue_step(p, p->capture_stream);
     hipGraph_t gobj = nullptr;
     hipError_t e = hipStreamEndCapture(p->capture_stream, &gobj);
     if (rc != ZG_OK) {
@@ -1088,13 +1140,14 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
     if (workspace_bytes < L.total) return fail(ZG_ENOMEM, "workspace smaller than zg_plan_query's workspace_bytes");
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(d_workspace);
-    const bool with_twin = (env->flags & ZG_PLAN_SAFE_TWIN) != 0;
+    const bool with_twin = (env->flags & (ZG_PLAN_SAFE_TWIN | ZG_PLAN_AUTO_FALLBACK)) != 0;
     zg_plan_t *p = nullptr;
     // with a twin the shared scratch is sized and cleared through the twin's (larger) layout
     rc = make_plan_object(&p, g, L, env->flags, batch, ws, st, !with_twin);
     if (rc != ZG_OK) return rc;
     if (with_twin) {
-        rc = make_plan_object(&p->twin, g, Ls, env->flags & ~ZG_PLAN_SAFE_TWIN, batch, ws, st, true);
+        rc = make_plan_object(&p->twin, g, Ls, env->flags & ~(ZG_PLAN_SAFE_TWIN | ZG_PLAN_AUTO_FALLBACK), batch, ws, st, true);
+        if (rc == ZG_OK && (env->flags & ZG_PLAN_AUTO_FALLBACK)) rc = build_graph(p); // again, now with the twin's kernels behind
         if (rc != ZG_OK) {
             zg_plan_destroy(p);
             return rc;
@@ -1123,8 +1176,8 @@ int zg_plan_bind_features(zg_plan_t *p, const float *d_feat, int64_t ld)
     if (!d_feat || ld < p->lay.feat_dim) return fail(ZG_EINVAL, "null feature table or ld < feat_dim");
     p->d_feat = d_feat;
     p->ld_feat = ld;
-    int rc = build_graph(p);
-    if (rc == ZG_OK && p->twin) rc = zg_plan_bind_features(p->twin, d_feat, ld);
+    int rc = p->twin ? zg_plan_bind_features(p->twin, d_feat, ld) : ZG_OK; // first: the plan's graph may hold the twin's kernels
+    if (rc == ZG_OK) rc = build_graph(p);
     return rc;
 }
 
@@ -1155,6 +1208,7 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
     o->log_capacity = kLogCapacity;
     o->d_epoch = &p->drmb()->epoch;
     o->x_row_cap = L.x_rows;
+    o->d_active = &p->drmb()->active;
     return ZG_OK;
 }
 
@@ -1173,7 +1227,7 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     p->issued += 1;
     int rc = ZG_OK;
     if (p->flags & ZG_PLAN_EAGER) {
-        rc = enqueue_body(p, st);
+        rc = enqueue_step(p, st);
     } else if (!p->graph_exec) {
         rc = fail(ZG_ESTATE, "plan has no captured graph");
     } else {
@@ -1188,6 +1242,8 @@ int zg_step_safe(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *s
 {
     if (!p) return fail(ZG_EINVAL, "null plan");
     if (!p->twin) return fail(ZG_ESTATE, "plan was made without ZG_PLAN_SAFE_TWIN");
+    if (p->flags & ZG_PLAN_AUTO_FALLBACK)
+        return fail(ZG_ESTATE, "with ZG_PLAN_AUTO_FALLBACK the twin runs inside zg_step, on the device's own decision");
     return zg_step(p->twin, d_seeds, rng_key, stream);
 }
 

@@ -96,7 +96,7 @@ int compute_layout(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops
     Layout L;
     int rc = compute_layout_one(g, fanouts, num_hops, batch, env, feat_dim, &pi, &L);
     if (rc != ZG_OK) return rc;
-    if (env->flags & ZG_PLAN_SAFE_TWIN) {
+    if (env->flags & (ZG_PLAN_SAFE_TWIN | ZG_PLAN_AUTO_FALLBACK)) { // the automatic fallback brings its twin
         zg_envelope worst = *env;
         worst.mode = ZG_ENV_MAX;
         zg_plan_info pis;

@@ -36,6 +36,7 @@ struct Drmb {
     uint32_t epoch;                    // steps run so far
     uint32_t key_lo, key_hi;           // step key
     uint32_t ticket[2 * ZG_MAX_HOPS];  // tile tickets: [2h] sampling, [2h+1] compaction
+    uint32_t active;                   // ZG_PLAN_AUTO_FALLBACK: 1 when the last step's valid outputs are the twin's
 };
 
 struct Layout {

@@ -17,7 +17,7 @@ LOG_STRIDE = 32
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 I32, I64 = 0, 1
 GRAPH_VALIDATE = 1
-PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN, PLAN_FUSED_INPUT = 1, 2, 4, 8
+PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN, PLAN_FUSED_INPUT, PLAN_AUTO_FALLBACK = 1, 2, 4, 8, 16
 ENV_MAX, ENV_MODEL, ENV_EXPLICIT = 0, 1, 2
 FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
 
@@ -61,7 +61,8 @@ class Outputs(C.Structure):
                 ("d_col", C.c_void_p * MAX_HOPS),
                 ("node_cap", C.c_int64 * (MAX_HOPS + 1)), ("edge_cap", C.c_int64 * MAX_HOPS),
                 ("d_X", C.c_void_p), ("ldx", C.c_int64), ("d_agg", C.c_void_p), ("ld_agg", C.c_int64),
-                ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p), ("x_row_cap", C.c_int64)]
+                ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p), ("x_row_cap", C.c_int64),
+                ("d_active", C.c_void_p)]
 
 
 _lib = None
@@ -383,6 +384,11 @@ class Plan:
     def epoch(self) -> int:
         import torch
         return int(self._view(self.out.d_epoch, 1, torch.int32).item())
+
+    def view_active(self):
+        """Device word of a PLAN_AUTO_FALLBACK plan: 1 if the last step's valid outputs are the twin's."""
+        import torch
+        return self._view(self.out.d_active, 1, torch.int32)
 
     def read_step(self, with_features: bool = True) -> StepResult:
         """Synchronise and copy the last step's outputs to the host (numpy)."""

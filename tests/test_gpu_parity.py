@@ -278,6 +278,60 @@ def test_safe_twin_fallback_reproduces_the_untruncated_step(oracle):
     assert ei.value.status == zg.ESTATE
 
 
+@pytest.mark.parametrize("eager", [False, True])
+def test_automatic_fallback_is_decided_on_the_device(oracle, eager):
+    # tight caps (the median of the last-hop sizes over 12 batches): about half of the steps overflow and are redone
+    # by the twin's gated kernels inside the same launch; the host only ever reads after the fact
+    g = W.rmat_graph(30_000, 600_000, 21)
+    og = to_host_graph(oracle, g)
+    feat = W.feature_table(30_000, 20, 4)
+    pool = W.SeedPool(g, 300, 2)
+    fan, steps = (8, 6), 12
+    seeds = [pool.batch_for(s).numpy() for s in range(steps)]
+    refs = [og.sample_blocks(seeds[s], fan, 500 + s) for s in range(steps)]
+    caps = [0, max(r.n[1] for r in refs), int(np.median([r.n[2] for r in refs]))]
+    flags = zg.PLAN_AUTO_FALLBACK | (zg.PLAN_EAGER if eager else 0)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    plan = zg.Plan(dg, fan, 300, zg.make_envelope(zg.ENV_EXPLICIT, flags=flags, node_caps=caps), feat_dim=20)
+    assert plan.info.safe_envelope_bytes > 0
+    plan.bind_features(feat.cuda())
+    twin = plan.safe_view()
+    fell_back = 0
+    for s in range(steps):
+        plan.step(torch.as_tensor(seeds[s]).cuda(), 500 + s)
+        torch.cuda.synchronize()
+        active = int(plan.view_active().item())
+        expect = 1 if refs[s].n[2] > caps[2] else 0
+        assert active == expect, (s, active, refs[s].n[2], caps[2])
+        done, fl = plan.step_status()
+        assert done == s + 1 and (fl != 0) == bool(expect)
+        view = twin if active else plan
+        res = view.read_step()
+        if active:
+            assert res.flags == 0
+        else:
+            res.flags &= ~zg.FLAG_HOP_OVERFLOW(1)  # the plan's sticky word remembers earlier overflows
+        compare_blocks(res, refs[s], f"step {s} active={active}")
+        compare_features(oracle, res, refs[s], feat.numpy(), f"step {s} active={active}")
+        fell_back += active
+    assert 0 < fell_back < steps
+    assert twin.epoch() == fell_back and plan.epoch() == steps
+    # several steps in a row without a sync: the twin's log holds exactly the overflowed steps, in order
+    for s in range(steps):
+        plan.step(torch.as_tensor(seeds[s]).cuda(), 500 + s)
+    torch.cuda.synchronize()
+    assert plan.step_status()[0] == 2 * steps
+    tlog = twin.view_log().cpu().numpy()
+    over = [s for s in range(steps) if refs[s].n[2] > caps[2]]
+    for k, s in enumerate(over):
+        rec = tlog[(fell_back + k) % tlog.shape[0]]
+        assert rec[1] == 0 and list(rec[2:5]) == refs[s].n and list(rec[5:7]) == refs[s].E, (k, s, rec[:8])
+    with pytest.raises(zg.ZgError) as ei:
+        plan.step_safe(torch.as_tensor(seeds[0]).cuda(), 1)
+    assert ei.value.status == zg.ESTATE
+
+
+
 @pytest.mark.parametrize("dim", [24, 600, 7])
 def test_fused_input_only_materialises_the_frontier_rows(oracle, dim):
     # X = rows of D_{H-1} only; the aggregation reads its input rows from the feature table: same numbers
