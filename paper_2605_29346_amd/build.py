@@ -1,4 +1,5 @@
-"""Builds libzg.so (the C-ABI library: HIP kernels for gfx950 + host planner) in-tree with hipcc."""
+"""Builds libzg.so (the C-ABI library: HIP kernels for gfx950 + host planner) in-tree with hipcc, and the
+stand-alone memory-ceiling probe zg_ceilings (its output is kept under profiles/)."""
 from __future__ import annotations
 
 import os
@@ -8,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libzg.so")
 SOURCES = [os.path.join(HERE, "csrc", f) for f in ("zg_host.cpp", "zg_device.hip")]
+CEILINGS = os.path.join(HERE, "zg_ceilings")
+CEILINGS_SRC = os.path.join(HERE, "csrc", "zg_ceilings.hip")
 HEADERS = [os.path.join(HERE, "csrc", "zg_internal.h"), os.path.join(ROOT, "include", "zg.h")]
 
 
@@ -25,6 +28,11 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    probe = [hipcc, "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-o", CEILINGS, CEILINGS_SRC]
+    if verbose:
+        print(" ".join(probe))
+    subprocess.run(probe, check=True)
     return LIB
 
 
