@@ -141,7 +141,7 @@ struct Mailbox {
 constexpr uint32_t kHopOverflowMask = 0xFFFFu;
 __device__ __forceinline__ bool gate_closed(const Drmb *gate)
 {
-    return gate != nullptr && (gate->step_flags & kHopOverflowMask) == 0u;
+    return gate != nullptr && (gate->last_flags & kHopOverflowMask) == 0u;
 }
 
 struct IngestArgs {
@@ -179,7 +179,6 @@ __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
         d->n_exact[0] = a.batch;
         d->key_lo = (uint32_t)(s_in[1] & 0xFFFFFFFFull);
         d->key_hi = (uint32_t)(s_in[1] >> 32);
-        d->step_flags = 0;
         for (int i = 0; i < 2 * ZG_MAX_HOPS; ++i) d->ticket[i] = 0;
     }
     for (uint64_t w = gtid; w < a.status_words; w += gsize) a.status[w] = 0;
@@ -585,8 +584,11 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         for (int h = 0; h < a.num_hops; ++h) rec[p++] = d->E[h];
         for (int h = 1; h <= a.num_hops; ++h) rec[p++] = d->n_exact[h];
         d->epoch = epoch + 1;
-        d->active = (d->step_flags & kHopOverflowMask) != 0u && a.defer_completed ? 1u : 0u;
-        __hip_atomic_store(&a.mailbox->status[epoch % kMailboxSlots], d->step_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        const uint32_t step_flags = d->step_flags;
+        d->last_flags = step_flags;
+        d->step_flags = 0; // for the next step: its first kernel raises seed bits from many lanes, so nobody resets there
+        d->active = (step_flags & kHopOverflowMask) != 0u && a.defer_completed ? 1u : 0u;
+        __hip_atomic_store(&a.mailbox->status[epoch % kMailboxSlots], step_flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (!a.defer_completed)
             __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         if (a.gate) publish_gate_owner(a);

@@ -33,6 +33,7 @@ struct Drmb {
     uint32_t n_exact[ZG_MAX_HOPS + 1]; // |S_{h-1}| before clamping
     uint32_t flags;                    // sticky ZG_FLAG_* bits
     uint32_t step_flags;               // the same bits, for the current step only
+    uint32_t last_flags;               // step_flags of the step that finished last (step_flags itself restarts at 0)
     uint32_t epoch;                    // steps run so far
     uint32_t key_lo, key_hi;           // step key
     uint32_t ticket[2 * ZG_MAX_HOPS];  // tile tickets: [2h] sampling, [2h+1] compaction

@@ -169,3 +169,6 @@ def test_plan_query_with_safe_twin_adds_the_worst_case_outputs_and_shares_the_sc
     assert both.scratch_bytes == worst.scratch_bytes  # one scratch region, sized for the twin
     assert both.workspace_bytes == tight.envelope_bytes + worst.envelope_bytes + worst.scratch_bytes
     assert list(both.node_cap[:3]) == list(tight.node_cap[:3])
+    # the device-side fallback brings the same twin with it
+    auto = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MODEL, flags=zg.PLAN_AUTO_FALLBACK), feat_dim=8)
+    assert (auto.safe_envelope_bytes, auto.workspace_bytes) == (both.safe_envelope_bytes, both.workspace_bytes)
