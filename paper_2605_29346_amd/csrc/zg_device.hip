@@ -8,6 +8,9 @@
 // from the device-resident metadata buffer and lets surplus workgroups return at once (paper
 // sections 4.1-4.3).  The whole step is one hipGraph (section 4.4); the step's seeds pointer and key reach it
 // through a mailbox in pinned host memory.
+// A plan may carry a worst-case twin (the paper's "cached safe graph", section 4.3) that replays a mini-batch
+// whose sizes overflowed the envelope, on the host's request or - its kernels appended to the step's graph
+// behind a device-side gate - by itself.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -253,7 +256,7 @@ struct SampleArgs {
 // vertices, G = 2^group_log2 lanes per vertex, one lane per sampled slot, so that no lane ever loops over
 // slots: the step is latency-bound at mini-batch sizes and the dependent chain (ticket, frontier id, two
 // offsets, chained scan, neighbor id, "seen" word) is what sets its time.  A workgroup takes one ticket for
-// 1..8 consecutive tiles (more for large frontiers, to keep the ticket counter cool).  The first T lanes
+// 1..4 consecutive tiles (more for large frontiers, to keep the ticket counter cool).  The first T lanes
 // compute k_i = min(F, deg) for all its tiles, their sum is chained to the predecessor tickets, then tile by
 // tile: local scan, row_ptr, and lane
 // (t, j) finds slot j's neighbor position of vertex t: j itself if deg <= F, else Floyd's subset algorithm

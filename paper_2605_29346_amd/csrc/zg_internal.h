@@ -50,7 +50,7 @@ struct Layout {
     int32_t fanout[ZG_MAX_HOPS] = {};
     int64_t bitmap_words = 0; // padded to whole compaction tiles
     int64_t sample_tiles[ZG_MAX_HOPS] = {};   // tiles of 1024 / G frontier vertices
-    int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..8)
+    int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..kSampleMaxTpt)
     int64_t sample_blocks[ZG_MAX_HOPS] = {};  // sampling workgroups = ceil(tiles / tiles per ticket)
     int32_t compact_sub = 1;                  // rounds of 1024 words per compaction tile (a power of two)
     int64_t compact_tiles = 0;
