@@ -149,3 +149,16 @@ def test_randomised_configurations(oracle):
             agg_ref = oracle.aggregate_mean(ref.row_ptr[-1], ref.col[-1], X_ref)
             assert agg_error(oracle, res.agg, agg_ref, ref.row_ptr[-1], ref.col[-1], X_ref) <= 1e-5, label
         plan.close()
+
+
+def test_worked_example_from_the_published_known_answer(oracle):
+    # vertex 0, slot 0, hop 0, key 0 is the all-zero Philox input (published output 6627e8d5 e169c58d ...): the draw is
+    # 0xe169c58d6627e8d5 = 0.88052 * 2^64, so one slot over d neighbors lands on position floor(0.88052 d)
+    x = 0xE169C58D6627E8D5
+    for d in (5, 3, 100, 1000):
+        expect = (x * d) >> 64
+        off = np.zeros(d + 2, dtype=np.int64)
+        off[1:] = d
+        g = W.Graph(d + 1, torch.as_tensor(off), torch.arange(1, d + 1, dtype=torch.int32))
+        _, res, _ = run_and_compare(oracle, g, None, np.array([0], dtype=np.int32), (1,), 0)
+        assert res.nbr_gid[0].tolist() == [expect + 1] and res.S.tolist() == [0, expect + 1]

@@ -45,6 +45,26 @@ def test_draw_is_keyed_by_key_hop_node_slot(oracle):
                 oracle.draw(5, 1, 7, 4), oracle.draw(5 + 2**32, 1, 7, 3)}) == 6
 
 
+def test_worked_example_from_the_published_known_answer(oracle):
+    # vertex 0, slot 0, hop 0, key 0 is the all-zero Philox input, whose output the fixture holds: the draw is
+    # out0 + 2^32 out1 = 0xe169c58d6627e8d5 = 0.88052... * 2^64.  With one slot and d neighbors the position is
+    # floor(0.88052 * d): 4 of 5, 2 of 3, 88 of 100 - worked out here from the fixture's words, not by the checker.
+    row = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"][0]
+    assert [int(x, 16) for x in row[:6]] == [0] * 6
+    x = int(row[6], 16) | (int(row[7], 16) << 32)
+    assert oracle.draw(0, 0, 0, 0) == x
+    for d, expect in ((5, 4), (3, 2), (2, 1), (100, 88), (1000, 880)):
+        assert (x * d) >> 64 == expect
+        assert oracle.sample_positions(0, 0, 0, d, 1) == [expect]
+        # the whole pipeline on a star: vertex 0 adjacent to 1..d, one seed, fanout 1, key 0
+        off = np.zeros(d + 2, dtype=np.int64)
+        off[1:] = d
+        g = oracle.Graph(off, np.arange(1, d + 1, dtype=np.int32))
+        b = g.sample_blocks(np.array([0], dtype=np.int32), (1,), 0)
+        assert b.n == [1, 2] and b.E == [1]
+        assert b.nbr_gid[0].tolist() == [expect + 1] and b.S.tolist() == [0, expect + 1] and b.col[0].tolist() == [1]
+
+
 # ---------------------------------------------------------------------------- Floyd subsets
 @pytest.mark.parametrize("deg,F", [(5, 3), (6, 2), (4, 3), (7, 4), (3, 1), (6, 5)])
 def test_floyd_resolution_is_exactly_uniform_over_subsets(oracle, deg, F):
