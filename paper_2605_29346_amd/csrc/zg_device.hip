@@ -461,10 +461,12 @@ struct CompactArgs {
     int32_t last_hop; // nothing is sampled from the vertices this hop adds: their "seen" bits are not needed
 };
 
-__global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_compact_hop(CompactArgs a)
 {
+    constexpr int kWaves = BLOCK / 64;
     __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[4];
+    __shared__ uint32_t s_wsum[kWaves];
     if (gate_closed(a.gate)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
@@ -473,7 +475,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     const uint32_t tile = s_tile;
     // lane `tid` owns `rounds` consecutive uint4 (4 * rounds words) of the tile, so ranks inside the tile follow
     // (lane, word) order and one workgroup scan of the lanes' counts is enough however large the tile is
-    const size_t q0 = ((size_t)tile * kBlock + tid) * a.rounds;
+    const size_t q0 = ((size_t)tile * BLOCK + tid) * a.rounds;
     const uint4 *bm = reinterpret_cast<const uint4 *>(a.bitmap);
 
     // ---- walk 1: this lane's count
@@ -488,7 +490,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_hop(CompactArgs a)
     __syncthreads();
     uint32_t wbase = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < kWaves; ++w) {
         if (w < wave) wbase += s_wsum[w];
         total += s_wsum[w];
     }
@@ -1020,7 +1022,10 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
         ca.hop = h;
         ca.last_hop = h == H - 1 ? 1 : 0;
         ca.rounds = (uint32_t)L.compact_sub;
-        hipLaunchKernelGGL(k_compact_hop, dim3((unsigned)L.compact_tiles), dim3(kBlock), 0, st, ca);
+        if (L.compact_block == kCompactBlockLarge)
+            hipLaunchKernelGGL(k_compact_hop<kCompactBlockLarge>, dim3((unsigned)L.compact_tiles), dim3(kCompactBlockLarge), 0, st, ca);
+        else
+            hipLaunchKernelGGL(k_compact_hop<kCompactBlockSmall>, dim3((unsigned)L.compact_tiles), dim3(kCompactBlockSmall), 0, st, ca);
         ZG_HIP(hipGetLastError());
     }
     // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all

@@ -217,11 +217,18 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     }
     {
         const int64_t words = (V + 31) / 32;
-        // compaction tiles: 1024 words per round, rounds doubled until the tile count fits the ticket budget
-        // (measured at 110 M vertices: 256-512 tiles are best; fewer, larger tiles only lengthen each workgroup's walk)
+        // compaction tiles: a workgroup of 256 lanes takes 1024 words per round; when the bitmap has more words than
+        // the ticket budget covers in one round, workgroups of 1024 lanes (4096 words per round, half the ticket
+        // budget) take over and rounds double until the tile count fits.  Measured: at 250 k vertices many small
+        // workgroups win (the expansion's scattered stores spread over more CUs: 7 vs 13 us); at 110 M vertices the
+        // large ones do (a short look-back chain: 210 tiles of 4 rounds, 262 vs 280 us per step).
+        const bool large = words > max_tickets * 4 * kCompactBlockSmall;
+        L.compact_block = large ? kCompactBlockLarge : kCompactBlockSmall;
+        const int64_t budget = large ? std::max<int64_t>(1, max_tickets / 2) : max_tickets;
+        const int64_t round_words = 4 * (int64_t)L.compact_block;
         L.compact_sub = 1;
-        while (L.compact_sub < 4096 && words > max_tickets * kCompactSubWords * L.compact_sub) L.compact_sub *= 2;
-        const size_t tile_words = (size_t)kCompactSubWords * L.compact_sub;
+        while (L.compact_sub < 4096 && words > budget * round_words * L.compact_sub) L.compact_sub *= 2;
+        const size_t tile_words = (size_t)round_words * L.compact_sub;
         L.bitmap_words = (int64_t)align_up((size_t)words, tile_words);
         L.compact_tiles = L.bitmap_words / (int64_t)tile_words;
     }

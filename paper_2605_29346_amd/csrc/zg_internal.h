@@ -13,7 +13,8 @@ namespace zg {
 
 constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts of 64)
 constexpr int kSampleBlock = 1024;      // threads per sampling workgroup: (1024 / G) frontier vertices x G slots
-constexpr int kCompactSubWords = 1024;  // bitmap words a compaction workgroup takes per round (one uint4 per thread)
+constexpr int kCompactBlockSmall = 256;  // threads per compaction workgroup (each takes one uint4 = 4 bitmap words per round) ...
+constexpr int kCompactBlockLarge = 1024; // ... and for bitmaps beyond the ticket budget of the small ones
 constexpr int kMaxTickets = 512;        // tiles are sized so that a kernel's ticket counter sees about this many atomics
 constexpr int kSampleMaxTpt = 4;        // most consecutive tiles a sampling workgroup takes per ticket
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
@@ -52,7 +53,8 @@ struct Layout {
     int64_t sample_tiles[ZG_MAX_HOPS] = {};   // tiles of 1024 / G frontier vertices
     int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..kSampleMaxTpt)
     int64_t sample_blocks[ZG_MAX_HOPS] = {};  // sampling workgroups = ceil(tiles / tiles per ticket)
-    int32_t compact_sub = 1;                  // rounds of 1024 words per compaction tile (a power of two)
+    int32_t compact_block = 256;              // threads per compaction workgroup
+    int32_t compact_sub = 1;                  // rounds (of 4 words per thread) per compaction tile (a power of two)
     int64_t compact_tiles = 0;
     // byte offsets into the workspace
     size_t off_drmb = 0, off_log = 0, off_S = 0;
