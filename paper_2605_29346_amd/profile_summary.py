@@ -111,6 +111,8 @@ def main() -> None:
     ap.add_argument("prefix")
     ap.add_argument("--skip-steps", type=int, default=10, help="warm-up steps to leave out of the busy fraction")
     ap.add_argument("--cmd", default="")
+    ap.add_argument("--window-only", action="store_true", help="per-kernel durations over the counted steps only")
+    ap.add_argument("--note", default="")
     args = ap.parse_args()
     trace = list(csv.DictReader(open(os.path.join(args.folder, f"{args.prefix}_kernel_trace.csv"))))
     ours = [r for r in trace if "zg::" in r["Kernel_Name"]]
@@ -119,24 +121,31 @@ def main() -> None:
     print("# rocprofv3 kernel-trace summary")
     if args.cmd:
         print(f"\ncommand: `{args.cmd}`")
+    if args.note:
+        print(f"\n{args.note}")
     print(f"\nkernel dispatches of the library: {len(ours)}; steps (ingest kernels): {len(ingest)}")
 
+    seg = None
+    if len(ingest) > args.skip_steps + 1:
+        first = ingest[args.skip_steps]
+        # steady-state window: from the first counted step's ingest to the end of the last step (stand-alone
+        # kernel launches after the last step are not part of the loop)
+        last = ingest[-1]
+        per_step = -(-(ingest[-1] - first) // (len(ingest) - 1 - args.skip_steps))
+        seg = ours[first: last + per_step]
+
     stats = defaultdict(list)
-    for r in ours:
+    for r in (seg if (args.window_only and seg) else ours):
         stats[short(r["Kernel_Name"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
     total = sum(sum(v) for v in stats.values())
+    where = f"the {len(ingest) - args.skip_steps} steps after the first {args.skip_steps}" if (args.window_only and seg) else "the whole run"
+    print(f"\nper-kernel durations over {where}:")
     print("\n| kernel | launches | avg us | min us | max us | share of library GPU time |")
     print("|---|---|---|---|---|---|")
     for k, v in sorted(stats.items(), key=lambda kv: -sum(kv[1])):
         print(f"| {k} | {len(v)} | {sum(v) / len(v) / 1e3:.2f} | {min(v) / 1e3:.2f} | {max(v) / 1e3:.2f} | {100 * sum(v) / total:.1f}% |")
 
-    if len(ingest) > args.skip_steps + 1:
-        first = ingest[args.skip_steps]
-        # steady-state window: from the first timed step's ingest to the end of the last step (stand-alone
-        # kernel launches after the last step are not part of the loop)
-        last = ingest[-1]
-        per_step = (ingest[-1] - first) // (len(ingest) - 1 - args.skip_steps)
-        seg = ours[first: last + per_step]
+    if seg:
         t0 = int(seg[0]["Start_Timestamp"])
         t1 = max(int(r["End_Timestamp"]) for r in seg)
         ivs = sorted((int(r["Start_Timestamp"]), int(r["End_Timestamp"])) for r in seg)
@@ -149,7 +158,7 @@ def main() -> None:
                 cur_e = max(cur_e, e)
         busy += cur_e - cur_s
         nsteps = len(ingest) - args.skip_steps
-        print(f"\nsteady state: {nsteps} steps, {per_step} kernels per step, wall {1e-3 * (t1 - t0):.1f} us "
+        print(f"\nsteady state: {nsteps} steps, about {per_step} kernels per step, wall {1e-3 * (t1 - t0):.1f} us "
               f"({1e-3 * (t1 - t0) / nsteps:.2f} us/step), union of kernel intervals {1e-3 * busy:.1f} us")
         print(f"\n**GPU-busy fraction = {100.0 * busy / (t1 - t0):.2f}%**")
 
