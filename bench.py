@@ -291,7 +291,14 @@ def main():
         "sizes": {"n_mean": n_steps.mean(0).tolist(), "n_min": n_steps.min(0).tolist(), "n_max": n_steps.max(0).tolist(),
                   "E_mean": E_steps.mean(0).tolist(), "node_cap": [int(info.node_cap[h]) for h in range(H + 1)],
                   "maxsg_nodes": [int(info.maxsg_nodes[h]) for h in range(H + 1)],
-                  "model_mean": [float(info.model_mean[h]) for h in range(H + 1)]},
+                  "model_mean": [float(info.model_mean[h]) for h in range(H + 1)],
+                  "model_sigma": [float(info.model_sigma[h]) for h in range(H + 1)],
+                  # the distribution of the last hop's size over the timed steps (the paper's appendix B histogram):
+                  # ten equal bins between min and max, the spread (max - min) / mean, and the cap's headroom over the max
+                  "n_H_histogram": np.histogram(n_steps[:, H], bins=10)[0].tolist(),
+                  "n_H_spread": float((n_steps[:, H].max() - n_steps[:, H].min()) / n_steps[:, H].mean()),
+                  "n_H_std_over_mean": float(n_steps[:, H].std() / n_steps[:, H].mean()),
+                  "cap_over_max": float(info.node_cap[H] / n_steps[:, H].max())},
         "memory": {"envelope_bytes": int(info.envelope_bytes), "scratch_bytes": int(info.scratch_bytes),
                    "maxsg_envelope_bytes": int(info.maxsg_envelope_bytes), "exact_bytes_mean": float(exact.mean()),
                    "exact_bytes_max": float(exact.max()), "envelope_over_exact_mean": float(info.envelope_bytes / exact.mean()),
