@@ -97,3 +97,44 @@ def test_very_large_full_size(oracle):
         pytest.skip("needs a GPU with at least 150 GiB")
     cfg = W.CONFIGS["very_large"]
     _run_config(oracle, cfg, steps=6, full_steps={0, 5}, table_on_host=False)
+
+
+def test_long_pipelined_run_matches_the_checker_step_by_step(oracle):
+    # the benchmark's launch pattern held for a long run: four plans (model envelope) on four streams, steps issued
+    # round-robin with no sync inside a chunk of 800; every step's sizes (n_h, E_h of every hop, flags) from the
+    # device-side logs against the checker.  ZG_SOAK_STEPS lengthens the run (12,000 steps take about 20 s).
+    from concurrent.futures import ThreadPoolExecutor
+    steps = int(os.environ.get("ZG_SOAK_STEPS", "1600"))
+    cfg = W.CONFIGS["medium_dense"]
+    g = cfg.build_graph(device="cuda")
+    feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device="cuda")
+    og = to_host_graph(oracle, g)
+    dg = zg.Graph(g.offsets, g.indices)
+    pool = cfg.seed_pool(g)
+    H, P, chunk = len(cfg.fanouts), 4, 800
+    plans, streams = [], []
+    for _ in range(P):
+        p = zg.Plan(dg, cfg.fanouts, cfg.batch, zg.make_envelope(zg.ENV_MODEL), feat_dim=cfg.dim)
+        p.bind_features(feat)
+        plans.append(p)
+        streams.append(zg.new_stream())
+    bad = []
+    with ThreadPoolExecutor(min(16, os.cpu_count() or 1)) as ex:
+        for c0 in range(0, steps, chunk):
+            c1 = min(steps, c0 + chunk)
+            batches = {s: pool.batch_for(s).contiguous() for s in range(c0, c1)}
+            torch.cuda.synchronize()
+            for s in range(c0, c1):
+                plans[s % P].step(batches[s], cfg.key_for(s), streams[s % P])
+            torch.cuda.synchronize()
+            logs = [p.view_log().cpu().numpy() for p in plans]
+
+            def check(s):
+                ref = og.sample_blocks(batches[s].cpu().numpy(), cfg.fanouts, cfg.key_for(s))
+                r = logs[s % P][(s // P) % logs[s % P].shape[0]]
+                return r[0] == s // P and r[1] == 0 and list(r[2:2 + H + 1]) == ref.n and list(r[2 + H + 1:2 + 2 * H + 1]) == ref.E
+            bad += [c0 + i for i, ok in enumerate(ex.map(check, range(c0, c1))) if not ok]
+            print(f"[soak] steps {c0}..{c1} checked, {len(bad)} mismatches", flush=True)
+    assert not bad, bad[:10]
+    for p in plans:
+        p.close()
