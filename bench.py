@@ -183,6 +183,14 @@ def main():
             ap_.close()
         del aplans
 
+    # extra: the envelope the graph-aware size model would provision (caps from the inclusion probabilities propagated
+    # over the graph itself instead of the lemma's degree-proportional draws), checked against the realised sizes below
+    t_gm = time.perf_counter()
+    genv = zg.graph_envelope(dg, cfg.fanouts, cfg.batch, seed_prob=pool.seed_prob(g.num_nodes))
+    torch.cuda.synchronize()
+    t_gm = time.perf_counter() - t_gm
+    ginfo = dg.plan_query(cfg.fanouts, cfg.batch, genv, feat_dim=cfg.dim)
+
     # realised sizes of the timed steps from the device-side log
     logrec = plan.view_log().cpu().numpy().astype(np.int64)
     total_steps = plan.epoch()
@@ -304,6 +312,12 @@ def main():
                    "exact_bytes_max": float(exact.max()), "envelope_over_exact_mean": float(info.envelope_bytes / exact.mean()),
                    "maxsg_over_envelope": float(info.maxsg_envelope_bytes / info.envelope_bytes),
                    "overflow_steps": int((recs[:, 1] != 0).sum())},
+        "graph_model_envelope": {"node_cap": [int(ginfo.node_cap[h]) for h in range(H + 1)],
+                                 "envelope_bytes": int(ginfo.envelope_bytes),
+                                 "envelope_over_exact_mean": float(ginfo.envelope_bytes / exact.mean()),
+                                 "cap_over_max": [float(ginfo.node_cap[h] / n_steps[:, h].max()) for h in range(1, H + 1)],
+                                 "would_overflow_steps": int((n_steps[:, 1:] > np.array([ginfo.node_cap[h] for h in range(1, H + 1)])).any(1).sum()),
+                                 "model_seconds": t_gm},
         "paper_context": "ZeroGNN reports up to 5.28x end-to-end speedup over DGL and ~100% GPU execution fraction on "
                          "NVIDIA A100 80GB (CUDA 11.7); ratios only, no absolute throughput",
     }

@@ -175,6 +175,21 @@ double zg_normal_quantile(double p);
 int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_distinct, const int32_t *fanouts,
                       int32_t num_hops, int32_t batch, int32_t with_replacement, double *mean, double *sigma);
 
+/* The same Poisson-binomial frame (the size of D_h as a sum of independent per-vertex indicators, appendix A)
+ * with inclusion probabilities taken from the graph instead of the degree-proportional assumption, which is
+ * crude when low-degree vertices hang on hubs: with q_u = P(u in D_h) and r_u the chance that a given neighbor
+ * of u is among u's picks at hop h (min(F_h, deg)/deg without replacement, 1 - (1 - 1/deg)^{F_h} with),
+ * P(v not in D_{h+1}) = (1 - q_v) prod_{u -> v} (1 - q_u r_u); mean[h+1] = sum_v q_v, sigma^2 = sum_v q_v(1 - q_v),
+ * mean[0] = batch, sigma[0] = 0.  Runs on the device, one sweep over the edges per hop, and synchronises with
+ * `stream` (plan time, once).  d_seed_prob: per-vertex probability of being a seed, fp32 [num_nodes] in device
+ * memory, or NULL for uniform seeds (batch / num_nodes).  d_temp: caller's device scratch, 256-byte aligned, at
+ * least 12 * num_nodes + 576 bytes; contents undefined afterwards.  The result is deterministic (integer sums).
+ * Turn it into caps with ZG_ENV_EXPLICIT: node_caps[h] = (1 + margin) * mean[h] (+ z sigma).
+ * Errors: ZG_EINVAL (arguments, buffer), ZG_ESTATE (statistics-only handle, other device), ZG_EHIP. */
+int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+                            int32_t with_replacement, const float *d_seed_prob, void *d_temp, size_t temp_bytes,
+                            void *stream, double *mean, double *sigma);
+
 /* ---- plan (section 4.3: one-time provisioning of the execution envelope) ------------------------
  * Host only.  Caps, launch caps and workspace size for (fanouts, batch, envelope, feat_dim);
  * feat_dim = 0 plans the sampling/relabel/CSR part only.  1 <= num_hops <= ZG_MAX_HOPS,

@@ -15,6 +15,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -774,6 +775,79 @@ __global__ void k_validate(const OffT *off, const int32_t *idx, int64_t num_node
     }
 }
 
+// ---- graph-aware size model (plan time) ---------------------------------------------------------
+// The size model of the paper's Lemma 1 treats every neighbor draw as an independent pick of a vertex with
+// probability proportional to its degree.  The kernels below keep its frame - the size of D_h is a sum of
+// independent indicators, one per vertex - but take each vertex's inclusion probability from the graph itself:
+// with q_u = P(u in D_h) and r_u = the chance that a given neighbor of u is among u's picks at hop h
+// (min(F, deg)/deg without replacement, 1 - (1 - 1/deg)^F with), a vertex v stays out of D_{h+1} with
+// probability (1 - q_v) * prod over its in-neighbors u of (1 - q_u r_u).  One sweep over the edges per hop.
+// Sums are kept as 64-bit fixed point (2^-32) so that the result does not depend on the order of the atomics.
+constexpr double kFix = 4294967296.0; // 2^32
+
+__global__ void k_model_init(float *q, unsigned long long *ell, const float *seed_prob, float uniform, int64_t n)
+{
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
+        float p = seed_prob ? seed_prob[v] : uniform;
+        p = p < 0.0f ? 0.0f : (p > 1.0f ? 1.0f : p);
+        q[v] = p;
+        ell[v] = 0ull;
+    }
+}
+
+// one wave per source vertex: every neighbor v of u receives -log(1 - q_u r_u)
+template <typename OffT>
+__global__ __launch_bounds__(kBlock) void k_model_push(const OffT *off, const int32_t *idx, const float *q, unsigned long long *ell,
+                                                       int64_t n, int32_t fanout, int32_t replace)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kBlock) >> 6;
+    for (int64_t u = wave0; u < n; u += waves) {
+        const float qu = q[u];
+        if (qu <= 0.0f) continue;
+        const int64_t b = (int64_t)off[u], e = (int64_t)off[u + 1];
+        const int64_t deg = e - b;
+        if (deg <= 0) continue;
+        double r;
+        if (replace)
+            r = -expm1((double)fanout * log1p(-1.0 / (double)deg));
+        else
+            r = deg <= fanout ? 1.0 : (double)fanout / (double)deg;
+        double x = (double)qu * r;
+        if (x > 1.0 - 1e-9) x = 1.0 - 1e-9;
+        const unsigned long long c = (unsigned long long)(-log1p(-x) * kFix);
+        if (c == 0ull) continue;
+        for (int64_t p = b + lane; p < e; p += 64) atomicAdd(&ell[idx[p]], c);
+    }
+}
+
+// q_v <- 1 - (1 - q_v) exp(-ell_v); ell_v <- 0; sums[0] += q_v, sums[1] += q_v (1 - q_v)
+__global__ __launch_bounds__(kBlock) void k_model_update(float *q, unsigned long long *ell, int64_t n, unsigned long long *sums)
+{
+    double a = 0.0, b = 0.0;
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n; v += (int64_t)gridDim.x * kBlock) {
+        const double l = (double)ell[v] / kFix;
+        const double q0 = (double)q[v];
+        const double q1 = q0 - (1.0 - q0) * expm1(-l);
+        q[v] = (float)q1;
+        ell[v] = 0ull;
+        a += q1;
+        b += q1 * (1.0 - q1);
+    }
+    // fixed-point before any cross-lane addition: integer sums are the same in any order
+    unsigned long long fa = (unsigned long long)(a * kFix), fb = (unsigned long long)(b * kFix);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        fa += __shfl_xor(fa, d, 64);
+        fb += __shfl_xor(fb, d, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicAdd(&sums[0], fa);
+        atomicAdd(&sums[1], fb);
+    }
+}
+
 #define ZG_HIP(call)                                                                                         \
     do {                                                                                                     \
         hipError_t e_ = (call);                                                                              \
@@ -1246,6 +1320,56 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     }
     if (rc != ZG_OK) p->issued -= 1; // nothing was enqueued: the slot is free again
     return rc;
+}
+
+int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, int32_t with_replacement,
+                            const float *d_seed_prob, void *d_temp, size_t temp_bytes, void *stream, double *mean, double *sigma)
+{
+    if (!g || !fanouts || !mean || !sigma || !d_temp) return fail(ZG_EINVAL, "null argument");
+    if (g->stats_only) return fail(ZG_ESTATE, "the graph-aware model needs a graph handle with device arrays");
+    if (num_hops < 1 || num_hops > ZG_MAX_HOPS) return fail(ZG_EINVAL, "num_hops must be in 1..ZG_MAX_HOPS");
+    if (batch < 1 || batch > g->num_nodes) return fail(ZG_EINVAL, "batch must be in 1..num_nodes");
+    for (int h = 0; h < num_hops; ++h)
+        if (fanouts[h] < 1 || fanouts[h] > ZG_MAX_FANOUT) return fail(ZG_EINVAL, "fanout must be in 1..ZG_MAX_FANOUT");
+    const int64_t n = g->num_nodes;
+    const size_t need = (size_t)n * 12 + 2 * kAlign + 64;
+    if ((reinterpret_cast<uintptr_t>(d_temp) % kAlign) != 0 || temp_bytes < need)
+        return fail(ZG_EINVAL, "temporary buffer must be 256-byte aligned and hold 12 bytes per vertex plus 576");
+    int device = -1;
+    ZG_HIP(hipGetDevice(&device));
+    if (device != g->device) return fail(ZG_ESTATE, "current device differs from the graph's device");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(d_temp);
+    unsigned long long *ell = reinterpret_cast<unsigned long long *>(base);
+    size_t at = (size_t)n * 8;
+    at = (at + kAlign - 1) / kAlign * kAlign;
+    float *q = reinterpret_cast<float *>(base + at);
+    at += (size_t)n * 4;
+    at = (at + kAlign - 1) / kAlign * kAlign;
+    unsigned long long *sums = reinterpret_cast<unsigned long long *>(base + at); // [2] per hop, reused
+    const int grid = (int)std::min<int64_t>(1 << 16, (n + kBlock - 1) / kBlock);
+    const int grid_push = (int)std::min<int64_t>(1 << 16, (n + (kBlock / 64) - 1) / (kBlock / 64));
+    hipLaunchKernelGGL(k_model_init, dim3(grid), dim3(kBlock), 0, st, q, ell, d_seed_prob, (float)((double)batch / (double)n), n);
+    ZG_HIP(hipGetLastError());
+    mean[0] = (double)batch;
+    sigma[0] = 0.0;
+    for (int h = 0; h < num_hops; ++h) {
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t *>(sums), 0u, (size_t)4);
+        if (g->offsets_dtype == ZG_I64)
+            hipLaunchKernelGGL(k_model_push<int64_t>, dim3(grid_push), dim3(kBlock), 0, st, (const int64_t *)g->d_offsets, g->d_indices, q,
+                               ell, n, fanouts[h], with_replacement);
+        else
+            hipLaunchKernelGGL(k_model_push<int32_t>, dim3(grid_push), dim3(kBlock), 0, st, (const int32_t *)g->d_offsets, g->d_indices, q,
+                               ell, n, fanouts[h], with_replacement);
+        hipLaunchKernelGGL(k_model_update, dim3(grid), dim3(kBlock), 0, st, q, ell, n, sums);
+        ZG_HIP(hipGetLastError());
+        unsigned long long host[2] = {0, 0};
+        ZG_HIP(hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, st));
+        ZG_HIP(hipStreamSynchronize(st));
+        mean[h + 1] = (double)host[0] / kFix;
+        sigma[h + 1] = std::sqrt((double)host[1] / kFix);
+    }
+    return ZG_OK;
 }
 
 int zg_step_safe(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream)

@@ -294,6 +294,16 @@ class SeedPool:
         chosen = self.hubs[pick].to(torch.int32)
         return torch.cat([chosen, plain[: self.batch - chosen.numel()]])
 
+    def seed_prob(self, num_nodes: int) -> torch.Tensor:
+        """float32 [num_nodes]: the chance that a vertex is a seed of a step picked at random (the pool's
+        vertices share the batch's places evenly; a hub enters with hub_prob)."""
+        p = torch.zeros(num_nodes, dtype=torch.float32, device=self.pool.device)
+        slots = self.pool.numel() // self.batch
+        p[self.pool[: slots * self.batch].long()] = 1.0 / slots
+        if self.hubs is not None:
+            p[self.hubs.long()] = self.hub_prob
+        return p
+
 
 # --------------------------------------------------------------------------------------
 # the five benchmark configurations

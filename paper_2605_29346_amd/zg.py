@@ -32,7 +32,7 @@ EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_s
            "zg_graph_degree_histogram", "zg_normal_quantile", "zg_envelope_model", "zg_plan_query", "zg_plan",
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
            "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
-           "zg_step_status"]
+           "zg_step_status", "zg_envelope_model_graph"]
 
 
 class Envelope(C.Structure):
@@ -102,6 +102,7 @@ def lib() -> C.CDLL:
         L.zg_step_safe.argtypes = [vp, vp, u64, vp]
         L.zg_plan_outputs_safe.argtypes = [vp, P(Outputs)]
         L.zg_step_status.argtypes = [vp, P(u32), P(u32)]
+        L.zg_envelope_model_graph.argtypes = [vp, P(i32), i32, i32, i32, vp, vp, C.c_size_t, vp, P(dbl), P(dbl)]
         for name in EXPORTS:
             if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile"):
                 getattr(L, name).restype = C.c_int
@@ -175,6 +176,35 @@ def _stream_ptr(stream) -> int:
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
+
+
+def graph_model(graph: "Graph", fanouts: Sequence[int], batch: int, *, with_replacement: bool = False, seed_prob=None,
+                stream=None):
+    """Mean and sigma of n_h from the graph-aware size model (computed on the device, synchronises)."""
+    import torch
+    H = len(fanouts)
+    f = (C.c_int32 * H)(*fanouts)
+    mean = (C.c_double * (MAX_HOPS + 1))()
+    sigma = (C.c_double * (MAX_HOPS + 1))()
+    nbytes = 12 * graph.num_nodes + 576
+    temp = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    base = (temp.data_ptr() + 255) // 256 * 256
+    sp = None
+    if seed_prob is not None:
+        assert seed_prob.is_cuda and seed_prob.dtype == torch.float32 and seed_prob.numel() == graph.num_nodes
+        sp = seed_prob.contiguous()
+    _check(lib().zg_envelope_model_graph(graph._h, f, H, batch, int(with_replacement), sp.data_ptr() if sp is not None else None,
+                                         base, nbytes, _stream_ptr(stream), mean, sigma))
+    return list(mean[: H + 1]), list(sigma[: H + 1])
+
+
+def graph_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, *, margin: float = 0.20, confidence: float = 0.999,
+                   iterations: int = 100_000, flags: int = 0, seed_prob=None) -> Envelope:
+    """Explicit caps from the graph-aware model: max((1 + margin) mean, mean + z sigma) per hop, z as in the lemma."""
+    mean, sigma = graph_model(graph, fanouts, batch, with_replacement=bool(flags & PLAN_REPLACE), seed_prob=seed_prob)
+    z = normal_quantile(confidence ** (1.0 / iterations))
+    caps = [0] + [int(max((1.0 + margin) * m, m + z * s)) + 1 for m, s in zip(mean[1:], sigma[1:])]
+    return make_envelope(ENV_EXPLICIT, flags=flags, node_caps=caps)
 
 
 def pilot_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, seed_batches, keys, *, margin: float = 0.20,

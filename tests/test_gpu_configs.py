@@ -28,7 +28,7 @@ def _need_gpu():
     zg.lib()
 
 
-def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True):
+def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True, graph_aware=False):
     t0 = time.time()
     g = cfg.build_graph(device="cuda")
     feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device="cuda")
@@ -37,7 +37,8 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
     og = to_host_graph(oracle, g)
     pool = cfg.seed_pool(g)
     dg = zg.Graph(g.offsets, g.indices)
-    plan = zg.Plan(dg, cfg.fanouts, cfg.batch, zg.make_envelope(env_mode), feat_dim=cfg.dim)
+    env = zg.graph_envelope(dg, cfg.fanouts, cfg.batch, seed_prob=pool.seed_prob(g.num_nodes)) if graph_aware else zg.make_envelope(env_mode)
+    plan = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
     plan.bind_features(feat)
     H = len(cfg.fanouts)
     batches = [pool.batch_for(s).contiguous() for s in range(steps)]
@@ -88,6 +89,15 @@ def test_large_sparse_full_size(oracle):
 def test_envelope_stress_full_size(oracle):
     cfg = W.CONFIGS["envelope_stress"]
     _run_config(oracle, cfg, steps=60, full_steps={0, 41})
+
+
+def test_envelope_stress_on_the_graph_aware_envelope(oracle):
+    # caps from the size model that propagates inclusion probabilities over the graph: a third of the lemma's envelope on
+    # this hub-heavy graph, and still no overflow (the run asserts clean status flags for every step)
+    cfg = W.CONFIGS["envelope_stress"]
+    plan, _ = _run_config(oracle, cfg, steps=100, full_steps={0, 77}, graph_aware=True)
+    lemma = plan.graph.plan_query(cfg.fanouts, cfg.batch, zg.make_envelope(zg.ENV_MODEL), feat_dim=cfg.dim)
+    assert plan.info.envelope_bytes < 0.5 * lemma.envelope_bytes
 
 
 @pytest.mark.skipif(os.environ.get("ZG_SKIP_VERY_LARGE") == "1", reason="ZG_SKIP_VERY_LARGE=1")

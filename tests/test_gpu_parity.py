@@ -408,3 +408,45 @@ def test_plans_in_flight_on_separate_streams(oracle):
         res = p.read_step()
         compare_blocks(res, last, f"plan {q}")
         compare_features(oracle, res, last, feat.numpy(), f"plan {q}")
+
+
+@pytest.mark.parametrize("i64,replace", [(False, False), (True, False), (True, True)])
+def test_graph_aware_size_model_matches_its_reference(oracle, i64, replace):
+    from oracle import zg_size_model as M
+    g = W.rmat_graph(50_000, 800_000, 12, offsets_dtype=torch.int64 if i64 else torch.int32)
+    off, idx = g.offsets.numpy().astype(np.int64), g.indices.numpy()
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    fan, batch = (9, 6, 4), 500
+    mean, sigma = zg.graph_model(dg, fan, batch, with_replacement=replace)
+    rmean, rsigma = M.graph_model(off, idx, fan, batch, with_replacement=replace)
+    assert mean[0] == batch and sigma[0] == 0
+    # fp32 storage of the probabilities and 2^-32 fixed-point sums on the device against plain fp64
+    assert np.allclose(mean, rmean, rtol=2e-5) and np.allclose(sigma, rsigma, rtol=2e-4), (mean, rmean, sigma, rsigma)
+    assert (mean, sigma) == tuple(zg.graph_model(dg, fan, batch, with_replacement=replace))  # integer sums: reproducible
+    # given seed probabilities: a fixed seed set and take-all fanouts give the breadth-first balls
+    seeds = np.random.RandomState(3).choice(50_000, 40, replace=False)
+    prob = torch.zeros(50_000)
+    prob[torch.as_tensor(seeds)] = 1.0
+    big = int(np.diff(off).max())
+    m2, s2 = zg.graph_model(dg, (min(big, 64), min(big, 64)), 40, seed_prob=prob.cuda())
+    if big <= 64:
+        ball = set(seeds.tolist())
+        for h in range(2):
+            ball |= {int(v) for u in list(ball) for v in idx[off[u]: off[u + 1]]}
+            assert abs(m2[h + 1] - len(ball)) < 1e-2
+    r2, _ = M.graph_model(off, idx, (min(big, 64), min(big, 64)), 40, seed_prob=prob.numpy())
+    assert np.allclose(m2, r2, rtol=2e-5)
+    # a plan provisioned from it: tighter than the lemma's envelope here, and no overflow over 30 steps
+    env = zg.graph_envelope(dg, fan, batch, flags=zg.PLAN_REPLACE if replace else 0)
+    lemma = dg.plan_query(fan, batch, zg.make_envelope(zg.ENV_MODEL, flags=zg.PLAN_REPLACE if replace else 0))
+    plan = zg.Plan(dg, fan, batch, env)
+    assert plan.info.envelope_bytes < lemma.envelope_bytes
+    og = to_host_graph(oracle, g)
+    pool = W.SeedPool(g, batch, 9)
+    for s in range(30):
+        plan.step(pool.batch_for(s).cuda(), 400 + s)
+    res = plan.read_step()
+    assert res.flags == 0
+    compare_blocks(res, og.sample_blocks(pool.batch_for(29).numpy(), fan, 429, with_replacement=replace), "graph-aware envelope")
+    with pytest.raises(zg.ZgError):
+        zg.graph_model(zg.Graph.from_degree_histogram([1, 2], [10, 10]), (2,), 4)

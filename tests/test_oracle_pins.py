@@ -347,3 +347,39 @@ def test_philox_against_a_second_transcription(oracle):
         ctr = [rnd.getrandbits(32) for _ in range(4)]
         key = [rnd.getrandbits(32) for _ in range(2)]
         assert oracle.philox4x32_10(ctr, key) == _philox_bigint(ctr, key)
+
+
+# ---------------------------------------------------------------------------- graph-aware size model
+def test_size_model_reference_reduces_to_the_bfs_ball_when_everything_is_certain():
+    # seeds given with probability one and fanouts that take every neighbor: every indicator is 0 or 1 and the
+    # expected size of D_h is the size of the ball of radius h around the seeds (breadth-first search, by hand here)
+    from oracle import zg_size_model as M
+    g = W.rmat_graph(3000, 9000, 41)
+    off, idx = g.offsets.numpy().astype(np.int64), g.indices.numpy()
+    seeds = np.random.RandomState(1).choice(3000, 20, replace=False)
+    prob = np.zeros(3000)
+    prob[seeds] = 1.0
+    big = int(np.diff(off).max())
+    mean, sigma = M.graph_model(off, idx, (big, big, big), 20, seed_prob=prob)
+    ball = set(seeds.tolist())
+    for h in range(3):
+        ball |= {int(v) for u in list(ball) for v in idx[off[u]: off[u + 1]]}
+        assert abs(mean[h + 1] - len(ball)) < 1e-4 and sigma[h + 1] < 1e-3, (h, mean, len(ball))
+
+
+@pytest.mark.parametrize("replace", [False, True])
+def test_size_model_reference_tracks_the_sampler(oracle, replace):
+    # statistical pin: the model's mean against the realised sizes of the checker's own sampler over 60 mini-batches of
+    # uniform seeds (first hop within 2 %; later hops the independence assumption errs on the high side, within 12 %)
+    from oracle import zg_size_model as M
+    g = W.rmat_graph(20_000, 400_000, 5)
+    off, idx = g.offsets.numpy().astype(np.int64), g.indices.numpy()
+    og = oracle.Graph(off, idx)
+    fan, batch = (8, 5), 256
+    rnd = np.random.RandomState(2)
+    sizes = np.array([og.sample_blocks(rnd.choice(20_000, batch, replace=False).astype(np.int32), fan, 300 + s,
+                                       with_replacement=replace).n for s in range(60)], dtype=np.float64)
+    mean, sigma = M.graph_model(off, idx, fan, batch, with_replacement=replace)
+    real = sizes.mean(0)
+    assert abs(mean[1] / real[1] - 1.0) < 0.02, (mean, real)
+    assert -0.02 < mean[2] / real[2] - 1.0 < 0.12, (mean, real)
