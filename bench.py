@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--workload", default="medium_dense")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; invalid as a result)")
     ap.add_argument("--env", default="model", choices=["model", "max"])
+    ap.add_argument("--eager", action="store_true", help="plans launch their kernels one by one instead of replaying a hipGraph "
+                    "(a comparison; the default and the reported configuration is the captured graph)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
@@ -98,7 +100,7 @@ def main():
     H = len(cfg.fanouts)
 
     def make_plan(mode, flags=0):
-        env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags)
+        env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags | (zg.PLAN_EAGER if args.eager else 0))
         p = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
         p.bind_features(feat)
         return p
@@ -286,7 +288,7 @@ def main():
         "dtype": "int32 ids / f32 features", "data": "synthetic",
         "config": {"workload": cfg.name, "graph": f"{cfg.kind} |V|={g.num_nodes} |E|={g.num_edges}",
                    "offsets": str(g.offsets.dtype).replace("torch.", ""), "feat_dim": cfg.dim, "batch": cfg.batch,
-                   "fanouts": list(cfg.fanouts), "envelope": env_mode, "launch": "1 ingest kernel + 1 hipGraph replay per step",
+                   "fanouts": list(cfg.fanouts), "envelope": env_mode, "launch": ("kernels launched one by one (--eager)" if args.eager else "1 hipGraph replay per step"),
                    "pipeline": f"{pipeline} plan(s) on {pipeline} stream(s), steps issued round-robin",
                    "host_syncs_in_timed_region": 1},
         "single_stream": {"value": K / wall_single, "ms_per_step": wall_single / K * 1e3},
