@@ -108,8 +108,11 @@ def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
 
 def test_randomised_configurations(oracle):
     # 40 random (graph, batch, hops, fanouts, feature width, envelope mode, replacement) draws, two steps each
-    rnd = np.random.RandomState(20260529)
-    for trial in range(40):
+    # (ZG_FUZZ_TRIALS runs more of them, ZG_FUZZ_SEED another sequence)
+    rnd = np.random.RandomState(int(os.environ.get("ZG_FUZZ_SEED", "20260529")))
+    for trial in range(int(os.environ.get("ZG_FUZZ_TRIALS", "40"))):
+        if trial and trial % 50 == 0:
+            print(f"[fuzz] {trial} trials done", flush=True)
         nodes = int(rnd.choice([50, 333, 2048, 7001, 40_000, 150_000]))
         avg_deg = float(rnd.choice([0.5, 3, 20, 120]))
         draws = max(64, int(nodes * avg_deg))
