@@ -172,3 +172,15 @@ def test_plan_query_with_safe_twin_adds_the_worst_case_outputs_and_shares_the_sc
     # the device-side fallback brings the same twin with it
     auto = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_MODEL, flags=zg.PLAN_AUTO_FALLBACK), feat_dim=8)
     assert (auto.safe_envelope_bytes, auto.workspace_bytes) == (both.safe_envelope_bytes, both.workspace_bytes)
+
+
+def test_graph_aware_model_rejects_bad_arguments_before_touching_a_device():
+    g = _stats_graph()
+    L = zg.lib()
+    mean = (ctypes.c_double * 9)()
+    sigma = (ctypes.c_double * 9)()
+    fan = (ctypes.c_int32 * 2)(5, 4)
+    # a statistics-only handle has no edges to sweep
+    assert L.zg_envelope_model_graph(g._h, fan, 2, 100, 0, None, 256, 10**9, None, mean, sigma) == zg.ESTATE
+    assert L.zg_envelope_model_graph(None, fan, 2, 100, 0, None, 256, 10**9, None, mean, sigma) == zg.EINVAL
+    assert L.zg_envelope_model_graph(g._h, fan, 2, 100, 0, None, None, 10**9, None, mean, sigma) == zg.EINVAL
