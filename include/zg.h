@@ -56,8 +56,10 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
 #define ZG_PLAN_EAGER 1u   /* launch the step's kernels one by one instead of replaying a hipGraph */
 #define ZG_PLAN_REPLACE 2u /* sample with replacement (the setting of the paper's Lemma 1) */
 #define ZG_PLAN_FUSED_INPUT 8u /* X holds the rows of the frontier D_{H-1} only and the aggregation reads its input rows
-                                 straight from the feature table: what the first GraphSAGE layer consumes, [X_self | mean],
-                                 with the rows that only feed the mean never written out */
+                                 straight from the feature table; the rows that only feed the mean are never written out.
+                                 X and agg are then the left and right halves of ONE row-major matrix at d_X, row i =
+                                 [X_self(i) | mean(i)] with row stride ldx = ld_agg = 2 * (feat_dim rounded up to 4) and
+                                 d_agg = d_X + ldx / 2: the input of the first GraphSAGE layer, ready for one GEMM */
 #define ZG_PLAN_SAFE_TWIN 4u /* also provision the worst-case twin of the plan: the paper's "cached safe graph" (section 4.3) */
 #define ZG_PLAN_AUTO_FALLBACK 16u /* (brings the twin) the step's captured graph also holds the twin's kernels, behind a
                                  device-side conditional: every workgroup of theirs returns at once unless the plan's own

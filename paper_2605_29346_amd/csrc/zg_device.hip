@@ -1112,15 +1112,15 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
     std::memset(&gat, 0, sizeof(gat));
     int vec = 1;
     if (feats) {
-        vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ldx) && aligned16(p->agg(), L.ldx) ? 4 : 1;
+        vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ld_out) && aligned16(p->agg(), L.ld_out) ? 4 : 1;
         int v1 = vec, v2 = vec;
         // ZG_PLAN_FUSED_INPUT: X stops at the frontier's rows, so the mean takes its input rows from the table,
         // addressed by the sampled global ids (feat[nbr_gid[e]] is the row X[col[e]] would have held)
         if (fused)
-            agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ldx, true, &v1);
+            agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ld_out, true, &v1);
         else
-            agg = aggregate_args(p, H - 1, p->X(), L.ldx, L.feat_dim, p->agg(), L.ldx, false, &v1);
-        gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ldx, fused ? H - 1 : H, &v2);
+            agg = aggregate_args(p, H - 1, p->X(), L.ld_out, L.feat_dim, p->agg(), L.ld_out, false, &v1);
+        gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, fused ? H - 1 : H, &v2);
         vec = v1; // both tilings take the same vector width for the same dim and alignment
     }
     int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true, gate), st);
@@ -1285,9 +1285,9 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
     }
     for (int h = 0; h <= L.num_hops; ++h) o->node_cap[h] = L.node_cap[h];
     o->d_X = p->X();
-    o->ldx = L.ldx;
+    o->ldx = L.ld_out;
     o->d_agg = p->agg();
-    o->ld_agg = L.ldx;
+    o->ld_agg = L.ld_out;
     o->d_log = p->log();
     o->log_capacity = kLogCapacity;
     o->d_epoch = &p->drmb()->epoch;

@@ -191,8 +191,10 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
             b += align_up((size_t)(node_cap[h] + 1) * 4, kAlign) + kGuard;
             b += 2 * (align_up((size_t)node_cap[h] * fanouts[h] * 4, kAlign) + kGuard);
         }
-        if (feat_dim > 0) {
-            b += align_up((size_t)node_cap[fused ? num_hops - 1 : num_hops] * ldx * 4, kAlign) + kGuard;
+        if (feat_dim > 0 && fused) { // one matrix [X_self | mean]
+            b += align_up((size_t)node_cap[num_hops - 1] * 2 * ldx * 4, kAlign) + kGuard;
+        } else if (feat_dim > 0) {
+            b += align_up((size_t)node_cap[num_hops] * ldx * 4, kAlign) + kGuard;
             b += align_up((size_t)node_cap[num_hops - 1] * ldx * 4, kAlign) + kGuard;
         }
         return (int64_t)b;
@@ -247,8 +249,16 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_nbr[h] = place((size_t)L.edge_cap[h] * 4);
         L.off_col[h] = place((size_t)L.edge_cap[h] * 4);
     }
-    if (feat_dim > 0) {
-        L.x_rows = L.node_cap[fused ? num_hops - 1 : num_hops];
+    L.ld_out = ldx;
+    if (feat_dim > 0 && fused) {
+        // the frontier's own rows and the mean of their sampled neighbors side by side, row i = [X_self(i) | mean(i)]:
+        // the input of the first GraphSAGE layer as one row-major matrix
+        L.x_rows = L.node_cap[num_hops - 1];
+        L.ld_out = 2 * ldx;
+        L.off_X = place((size_t)L.x_rows * 2 * ldx * 4);
+        L.off_agg = L.off_X + (size_t)ldx * 4;
+    } else if (feat_dim > 0) {
+        L.x_rows = L.node_cap[num_hops];
         L.off_X = place((size_t)L.x_rows * ldx * 4);
         L.off_agg = place((size_t)L.node_cap[num_hops - 1] * ldx * 4);
     }

@@ -44,7 +44,8 @@ struct Drmb {
 struct Layout {
     int32_t num_hops = 0;
     int32_t feat_dim = 0;
-    int64_t ldx = 0; // row stride of X and agg in elements (feat_dim rounded up to 4)
+    int64_t ldx = 0; // feat_dim rounded up to 4 elements
+    int64_t ld_out = 0; // row stride of X and agg in elements: ldx, or 2 * ldx when they are the halves of one matrix
     int64_t x_rows = 0; // rows of X: node_cap[H], or node_cap[H-1] when only the frontier's rows are materialised
     int64_t node_cap[ZG_MAX_HOPS + 1] = {};
     int64_t edge_cap[ZG_MAX_HOPS] = {};

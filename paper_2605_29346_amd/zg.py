@@ -397,15 +397,20 @@ class Plan:
                 self._view(self.out.d_nbr_gid[h], self.out.edge_cap[h], torch.int32),
                 self._view(self.out.d_col[h], self.out.edge_cap[h], torch.int32))
 
-    def view_X(self):
+    def _rows_view(self, ptr: int, rows: int, ld: int):
+        """[rows, ld] strided fp32 view starting at a device address inside the workspace (the last row may end
+        before a full stride when two matrices interleave)."""
         import torch
-        H = self.num_hops
-        return self._view(self.out.d_X, self.out.x_row_cap * self.out.ldx, torch.float32).view(-1, self.out.ldx)
+        off = (ptr - self.workspace.data_ptr()) // 4
+        flat = self.workspace.view(torch.float32)
+        width = min(ld, flat.numel() - off - (rows - 1) * ld) if rows > 0 else ld
+        return torch.as_strided(flat, (rows, width), (ld, 1), off)
+
+    def view_X(self):
+        return self._rows_view(self.out.d_X, self.out.x_row_cap, self.out.ldx)
 
     def view_agg(self):
-        import torch
-        H = self.num_hops
-        return self._view(self.out.d_agg, self.out.node_cap[H - 1] * self.out.ld_agg, torch.float32).view(-1, self.out.ld_agg)
+        return self._rows_view(self.out.d_agg, self.out.node_cap[self.num_hops - 1], self.out.ld_agg)
 
     def view_log(self):
         import torch

@@ -355,6 +355,13 @@ def test_fused_input_only_materialises_the_frontier_rows(oracle, dim):
         assert np.array_equal(res.X.view(np.uint32), X_ref[: ref.n[1]].view(np.uint32))
         agg_ref = oracle.aggregate_mean(ref.row_ptr[-1], ref.col[-1], X_ref)
         assert agg_error(oracle, res.agg, agg_ref, ref.row_ptr[-1], ref.col[-1], X_ref) <= 1e-5
+    # X and the mean are the two halves of one row-major matrix: row i = [X_self(i) | mean(i)], the first layer's input
+    o = fused.out
+    half = o.ldx // 2
+    assert o.ldx == o.ld_agg == 2 * ((dim + 3) // 4 * 4) and o.d_agg == o.d_X + 4 * half
+    both = fused.view_X()[: ref.n[1]].cpu().numpy()
+    assert np.array_equal(both[:, :dim].view(np.uint32), res.X.view(np.uint32))
+    assert np.array_equal(both[:, half: half + dim].view(np.uint32), res.agg.view(np.uint32))
 
 
 def test_pilot_envelope_is_tight_and_does_not_overflow(oracle):
