@@ -55,7 +55,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="medium_dense")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; invalid as a result)")
-    ap.add_argument("--env", default="model", choices=["model", "max"])
+    ap.add_argument("--env", default="model", choices=["model", "max", "graph"],
+                    help="envelope of the plans: the paper's Lemma 1 from the degree histogram (default), the worst case, or "
+                         "explicit caps from the graph-aware size model")
     ap.add_argument("--eager", action="store_true", help="plans launch their kernels one by one instead of replaying a hipGraph "
                     "(a comparison; the default and the reported configuration is the captured graph)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -100,7 +102,11 @@ def main():
     H = len(cfg.fanouts)
 
     def make_plan(mode, flags=0):
-        env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags | (zg.PLAN_EAGER if args.eager else 0))
+        flags |= zg.PLAN_EAGER if args.eager else 0
+        if mode == "graph":
+            env = zg.graph_envelope(dg, cfg.fanouts, cfg.batch, flags=flags, seed_prob=pool.seed_prob(g.num_nodes))
+        else:
+            env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags)
         p = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
         p.bind_features(feat)
         return p
@@ -129,8 +135,8 @@ def main():
     plan = make_plan(env_mode)
     cur = torch.cuda.current_stream()
     wall_single = run([plan], [cur])
-    if flags_of([plan]) and env_mode == "model":
-        log(f"[bench] model envelope overflowed (flags {flags_of([plan]):#x}); re-running on the worst-case envelope")
+    if flags_of([plan]) and env_mode != "max":
+        log(f"[bench] the {env_mode} envelope overflowed (flags {flags_of([plan]):#x}); re-running on the worst-case envelope")
         env_mode = "max"
         plan = make_plan(env_mode)
         wall_single = run([plan], [cur])
@@ -170,7 +176,7 @@ def main():
     # extra: what the device-side fallback conditional costs when it never fires (the twin's gated kernels
     # return at once; the plan itself is the same model envelope)
     auto_fb = None
-    if not args.no_fused and env_mode == "model":
+    if not args.no_fused and env_mode != "max":
         aplans = [make_plan(env_mode, zg.PLAN_AUTO_FALLBACK) for _ in range(max(1, args.pipeline))]
         astreams = [zg.new_stream() for _ in aplans]
         torch.cuda.synchronize()
