@@ -76,7 +76,10 @@ def main():
     from paper_2605_29346_amd import workloads as W
     from paper_2605_29346_amd import zg
 
-    zg.lib()  # fail loudly if the HIP library is missing
+    from paper_2605_29346_amd import build as zg_build
+    if not os.path.exists(zg_build.LIB):  # load what is built; build only if nothing is
+        zg_build.build(force=True)
+    zg.lib()  # fails loudly if the HIP library still cannot be loaded: there is no other path
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
