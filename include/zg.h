@@ -25,9 +25,7 @@
  *    (The paper names the mini-batch side of a hop the source set V_s and the sampled side the
  *    destination set V_d.)
  *  - fanouts[h] applies at hop h (fanouts[0] to the seeds).
- *  - Environment: ZG_MAX_TICKETS (default 512) bounds how many workgroups of one kernel take a tile id
- *    from a shared atomic counter; tiles grow to stay below it.  A tuning knob read at plan time; results
- *    do not depend on it.
+ *  - The library reads no environment variable; every knob is a field of zg_envelope.
  */
 #ifndef ZG_H
 #define ZG_H
@@ -76,19 +74,27 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
 #define ZG_FLAG_INTERNAL (1u << 18)         /* a bounded device-side wait ran out (should never happen) */
 
 enum zg_env_mode {
-    ZG_ENV_MAX = 0,     /* worst case n_{h+1} = min(|V|, n_h (1 + F_h)): Eq. 1 applied hop by hop; never overflows */
-    ZG_ENV_MODEL = 1,   /* Lemma 1: Poisson-binomial mean/sigma of the deduplicated size, plus margin */
-    ZG_ENV_EXPLICIT = 2 /* caller's per-hop vertex caps (e.g. from a pilot run) */
+    ZG_ENV_MAX = 0,      /* worst case n_{h+1} = min(|V|, n_h (1 + F_h)): Eq. 1 applied hop by hop; never overflows */
+    ZG_ENV_MODEL = 1,    /* Lemma 1: Poisson-binomial mean/sigma of the deduplicated size from the degree histogram,
+                            cap = ceil(max((1 + margin) mean, mean + z sigma)) */
+    ZG_ENV_EXPLICIT = 2, /* caller's per-hop vertex caps (e.g. zg_envelope_from_pilot) */
+    ZG_ENV_GRAPH = 3     /* the same cap formula as ZG_ENV_MODEL applied to the caller's model_mean / model_sigma
+                            (the output of zg_envelope_model_graph) */
 };
 
 /* Execution envelope request (section 4.3, "Metadata-Free Dispatcher"). */
 typedef struct {
     int32_t mode;       /* zg_env_mode */
     uint32_t flags;     /* ZG_PLAN_* */
-    double margin;      /* ZG_ENV_MODEL: relative head-room over the model mean; < 0 selects 0.20 (appendix B) */
-    double confidence;  /* ZG_ENV_MODEL: p of z = Phi^-1(p^(1/m)); <= 0 selects 0.9999 */
-    int64_t iterations; /* ZG_ENV_MODEL: m; <= 0 selects 1000 */
+    double margin;      /* ZG_ENV_MODEL, ZG_ENV_GRAPH: relative head-room over the model mean; < 0 selects 0.20 (appendix B) */
+    double confidence;  /* ZG_ENV_MODEL, ZG_ENV_GRAPH: p of z = Phi^-1(p^(1/m)); <= 0 selects 0.9999 */
+    int64_t iterations; /* ZG_ENV_MODEL, ZG_ENV_GRAPH: m; <= 0 selects 1000 */
     int64_t node_caps[ZG_MAX_HOPS + 1]; /* ZG_ENV_EXPLICIT: cap of n_h for h = 1..H ([0] ignored); clamped to the worst case */
+    double model_mean[ZG_MAX_HOPS + 1];  /* ZG_ENV_GRAPH: mean of n_h, h = 1..H ([0] ignored) */
+    double model_sigma[ZG_MAX_HOPS + 1]; /* ZG_ENV_GRAPH: sigma of n_h */
+    int32_t max_tickets; /* tuning knob, <= 0 selects 512: how many workgroups of one kernel may take a tile id from a
+                            shared atomic counter (tiles grow to stay below it).  Results do not depend on it. */
+    int32_t reserved;
 } zg_envelope;
 
 /* Host-side answer of zg_plan_query. */
@@ -186,11 +192,18 @@ int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_d
  * `stream` (plan time, once).  d_seed_prob: per-vertex probability of being a seed, fp32 [num_nodes] in device
  * memory, or NULL for uniform seeds (batch / num_nodes).  d_temp: caller's device scratch, 256-byte aligned, at
  * least 12 * num_nodes + 576 bytes; contents undefined afterwards.  The result is deterministic (integer sums).
- * Turn it into caps with ZG_ENV_EXPLICIT: node_caps[h] = (1 + margin) * mean[h] (+ z sigma).
+ * Turn it into caps with ZG_ENV_GRAPH: copy mean / sigma into zg_envelope.model_mean / model_sigma; the planner
+ * applies the cap formula of section 4.3 / Lemma 1 (margin and z) to them.
  * Errors: ZG_EINVAL (arguments, buffer), ZG_ESTATE (statistics-only handle, other device), ZG_EHIP. */
 int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
                             int32_t with_replacement, const float *d_seed_prob, void *d_temp, size_t temp_bytes,
                             void *stream, double *mean, double *sigma);
+
+/* Envelope from a pilot run (section 4.4 warm-up iterations; appendix B observes realised sizes within a few
+ * percent of each other): `largest[h]`, h = 1..H, is the largest n_h seen over the pilot's mini-batches ([0]
+ * ignored).  Fills *out as a ZG_ENV_EXPLICIT request with node_caps[h] = ceil((1 + margin) * largest[h]),
+ * margin < 0 selecting 0.20, and the given ZG_PLAN_* flags.  Host only.  Errors: ZG_EINVAL. */
+int zg_envelope_from_pilot(const int64_t *largest, int32_t num_hops, double margin, uint32_t flags, zg_envelope *out);
 
 /* ---- plan (section 4.3: one-time provisioning of the execution envelope) ------------------------
  * Host only.  Caps, launch caps and workspace size for (fanouts, batch, envelope, feat_dim);
@@ -209,7 +222,9 @@ int zg_plan_query(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops,
  * pinned host memory), ZG_ESTATE (statistics-only graph handle, other device), ZG_EHIP.  *p is NULL on failure. */
 int zg_plan(zg_plan_t **p, const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
             const zg_envelope *env, int32_t feat_dim, void *d_workspace, size_t workspace_bytes, void *stream);
-/* Waits for the device to go idle (a step in flight still uses the plan), then releases the plan. */
+/* Waits until the plan's own last step has finished (its completion counter in pinned host memory, then the
+ * stream that step was issued on; other plans' streams are left alone), then releases the plan.  If the device
+ * does not finish within 30 s the call falls back to hipDeviceSynchronize. */
 int zg_plan_destroy(zg_plan_t *p);
 /* Makes gather + aggregation (section 2.2, "feature copy" and the first GraphSAGE aggregation) part of the
  * step: d_feat is the [num_nodes, ld] fp32 table in device memory (row stride ld elements, >= feat_dim),
@@ -226,11 +241,13 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *out);
  * writes (d_seeds, rng_key) into a slot of a small ring in pinned host memory that the step's first
  * kernel reads, and enqueues exactly ONE hipGraph launch - nothing else.  It never synchronises with
  * the device and never allocates; only when 255 earlier steps of this plan are still unfinished does
- * it wait, on the host, for the oldest one (a counter the device publishes in the same pinned ring).
+ * it wait, on the host, for the oldest one (a counter the device publishes in the same pinned ring); that
+ * wait is bounded: after 30 s without progress the call returns ZG_ESTATE and enqueues nothing.
  * Results are in the plan's output buffers once `stream` reaches this point.  Steps of one plan must be
  * stream-ordered one after another and issued from one host thread at a time.  Invalid seeds do not fault:
  * they raise ZG_FLAG_SEED_* bits in the device status word and make the step's outputs undefined.
- * Errors: ZG_EINVAL (null), ZG_ESTATE (no captured graph), ZG_EHIP (launch failed; nothing was enqueued). */
+ * Errors: ZG_EINVAL (null), ZG_ESTATE (no captured graph; device made no progress for 30 s), ZG_EHIP (launch
+ * failed; nothing was enqueued). */
 int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream);
 /* Stand-alone feature gather (section 2.2, "feature copy") for the vertex list the plan's last step left
  * on the device: d_out[i,:] = d_feat[S[i],:], i < n_H (n_H is read on the device); rows >= n_H of d_out are
@@ -257,11 +274,25 @@ int zg_plan_outputs_safe(const zg_plan_t *p, zg_outputs *out);
  * of every step writes, so a caller that already knows step k has finished (its own event or sync) can
  * decide about the fallback without reading device memory. */
 int zg_step_status(const zg_plan_t *p, uint32_t *steps_completed, uint32_t *last_flags);
+/* Pilot bookkeeping (plan time): waits for `stream`, reads the unclamped sizes n_h of the plan's last step and
+ * folds them into largest[0..H] by maximum (the caller zeroes the array before the first mini-batch).  Use it
+ * on a ZG_ENV_MAX plan and pass the result to zg_envelope_from_pilot.  Synchronises.  Errors: ZG_EINVAL, ZG_EHIP. */
+int zg_pilot_update(const zg_plan_t *p, int64_t *largest, void *stream);
 /* Section 4.3, "overflow-safe fallback": device address of the plan's sticky status word (ZG_FLAG_* bits
  * accumulate over steps).  The caller reads it when it chooses (async copy + event, end of an epoch).  Host only. */
 int zg_overflow_flag(const zg_plan_t *p, const uint32_t **d_flag);
 /* Clears the sticky word with a one-lane kernel on `stream` (no memset node: safe under graph capture). */
 int zg_overflow_clear(zg_plan_t *p, void *stream);
+
+
+/* ---- measurement helpers ----------------------------------------------------------------------
+ * Identifier of the sources the library was built from (a hash the build step passes in); lets a caller
+ * detect a stale binary.  Library-owned string. */
+const char *zg_build_id(void);
+/* A plain streaming copy d_dst[i] = d_src[i] over `bytes` bytes (a multiple of 16, both pointers 16-byte
+ * aligned, device memory), one kernel on `stream`: it reads `bytes` and writes `bytes` of HBM, which calibrates
+ * hardware traffic counters read for the library's other kernels.  Errors: ZG_EINVAL, ZG_EHIP. */
+int zg_calibration_copy(const void *d_src, void *d_dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,11 +15,13 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstring>
 #include <new>
 #include <thread>
 
+#include "zg_floyd.h"
 #include "zg_internal.h"
 
 namespace zg {
@@ -64,7 +66,7 @@ __device__ __forceinline__ uint64_t st_load(uint64_t *p)
 // every predecessor is already running) publishes its total, then wave 0 walks back over the
 // predecessors' status words, 64 at a time, until it meets a published inclusive prefix.  A status word
 // carries state and value together, so one relaxed 64-bit access is enough.  The wait is bounded.
-__device__ uint32_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, uint32_t total, uint32_t *flags, int lane)
+__device__ uint32_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, uint32_t total, Drmb *d, int lane)
 {
     if (lane == 0) st_store(&status[tile], (tile == 0 ? kStPrefix : kStAggregate) | total);
     uint32_t excl = 0;
@@ -79,7 +81,10 @@ __device__ uint32_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, ui
                 const bool invalid = (st >> 62) == 0;
                 if (!__any(invalid)) break;
                 if (++spins > kSpinLimit) {
-                    if (lane == 0) atomicOr(flags, ZG_FLAG_INTERNAL);
+                    if (lane == 0) { // the step's outputs are invalid: both the sticky and the per-step word say so
+                        atomicOr(&d->flags, ZG_FLAG_INTERNAL);
+                        atomicOr(&d->step_flags, ZG_FLAG_INTERNAL);
+                    }
                     if (invalid) st = kStAggregate;
                     break;
                 }
@@ -119,6 +124,15 @@ __device__ __forceinline__ uint64_t philox_draw(uint32_t key_lo, uint32_t key_hi
     }
     return (uint64_t)c0 | ((uint64_t)c1 << 32);
 }
+
+// The G lanes of a wavefront that hold the slots of one frontier vertex, as the group interface of
+// floyd_position (zg_floyd.h): slot j of the group sits in lane gbase + j.
+struct WaveGroup {
+    int gbase;
+    __device__ __forceinline__ uint32_t candidate_of(uint32_t j, uint32_t mine) const { return __shfl(mine, gbase + (int)j, 64); }
+    __device__ __forceinline__ bool flag_of(uint32_t j, bool mine) const { return __shfl((int)mine, gbase + (int)j, 64) != 0; }
+    __device__ __forceinline__ bool any(bool b) const { return __any(b) != 0; }
+};
 
 // =================================================================================================
 // kernels
@@ -335,7 +349,7 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, Relab
     __syncthreads();
     if (wave == 0) {
         const uint32_t ticket_total = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
-        const uint32_t e = chained_exclusive_prefix(a.status, ticket, ticket_total, &d->flags, lane);
+        const uint32_t e = chained_exclusive_prefix(a.status, ticket, ticket_total, d, lane);
         if (lane == 0) s_base = e;
     }
     __syncthreads();
@@ -391,28 +405,12 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, Relab
         } else {
             const bool floyd = slot && tdeg > F;
             if (__any(floyd)) {
-                const uint32_t tail0 = tdeg - F; // candidates >= tail0 coincide with the fallback value of slot cand-tail0
                 uint32_t cand = (uint32_t)gl;
                 if (floyd)
                     cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
-                                                (uint64_t)(tail0 + (uint32_t)gl) + 1ull);
-                bool dup = false;
-                for (uint32_t jj = 0; jj + 1 < F; ++jj) {
-                    const uint32_t cj = __shfl(cand, gbase + (int)jj, 64);
-                    dup = dup || (jj < (uint32_t)gl && cj == cand);
-                }
-                dup = dup && floyd;
-                const uint32_t a_i = cand - tail0; // meaningful only when cand >= tail0
-                const bool chase = floyd && cand >= tail0 && a_i < (uint32_t)gl;
-                bool collide = dup;
-                for (uint32_t it = 0; it < F; ++it) {
-                    const int ca = __shfl((int)collide, gbase + (int)(chase ? a_i : 0u), 64);
-                    const bool nc = dup || (chase && ca != 0);
-                    const bool changed = nc != collide;
-                    collide = nc;
-                    if (!__any(changed)) break;
-                }
-                pos = floyd ? (collide ? tail0 + (uint32_t)gl : cand) : (uint32_t)gl;
+                                                (uint64_t)(tdeg - F + (uint32_t)gl) + 1ull);
+                WaveGroup grp{gbase};
+                pos = floyd_position(grp, (uint32_t)gl, F, tdeg, floyd, cand);
             }
         }
         if (slot) {
@@ -496,7 +494,7 @@ __global__ __launch_bounds__(BLOCK) void k_compact_hop(CompactArgs a)
         total += s_wsum[w];
     }
     if (wave == 0) {
-        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, &d->flags, lane);
+        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, d, lane);
         if (lane == 0) s_base = e;
     }
     __syncthreads();
@@ -754,6 +752,12 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs agg, FinishArgs fi
         finish_block(fin, blockIdx.x - agg.blocks);
 }
 
+// plain streaming copy of 16-byte pieces: the traffic counters' calibration kernel (zg_calibration_copy)
+__global__ __launch_bounds__(kBlock) void k_calibrate_copy(const uint4 *src, uint4 *dst, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
+}
+
 __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
@@ -895,6 +899,8 @@ struct zg_plan_s {
     Mailbox *mailbox = nullptr;     // pinned host memory
     Mailbox *mailbox_dev = nullptr; // the same memory as the device addresses it
     uint32_t issued = 0;            // steps enqueued so far (mod 2^32, like the device-side step counter)
+    hipStream_t last_stream = nullptr; // stream of the last enqueued step (what zg_plan_destroy waits for)
+    bool stepped = false;
     zg_plan_s *twin = nullptr;      // worst-case twin (ZG_PLAN_SAFE_TWIN): own outputs, metadata and mailbox, shared scratch
     hipStream_t capture_stream = nullptr;
     hipGraph_t graph_obj = nullptr;
@@ -1241,10 +1247,33 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
     return ZG_OK;
 }
 
+// host-only wait until the device has published `target` finished steps of the plan; false after `seconds`
+static bool wait_completed(const zg_plan_t *p, uint32_t target, double seconds)
+{
+    const volatile uint32_t *done = &p->mailbox->completed;
+    const auto t0 = std::chrono::steady_clock::now();
+    uint32_t polls = 0;
+    while ((int32_t)(*done - target) < 0) {
+        std::this_thread::yield();
+        if ((++polls & 1023u) == 0 && std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > seconds) return false;
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return true;
+}
+
+constexpr double kHostWaitSeconds = 30.0;
+
 int zg_plan_destroy(zg_plan_t *p)
 {
     if (!p) return ZG_OK;
-    (void)hipDeviceSynchronize(); // a step still in flight reads the mailbox and the graph
+    // a step still in flight reads the mailbox and the captured graph: wait for this plan's own last step - its
+    // completion counter first (host memory only), then the stream it was issued on, so that the launch has
+    // retired as a whole.  Other plans' streams are not waited for.
+    if (p->mailbox && p->stepped) {
+        const bool done = wait_completed(p, p->issued, kHostWaitSeconds);
+        if (!done || hipStreamSynchronize(p->last_stream) != hipSuccess) (void)hipDeviceSynchronize();
+        (void)hipGetLastError();
+    }
     if (p->twin) zg_plan_destroy(p->twin);
     drop_graph(p);
     if (p->capture_stream) (void)hipStreamDestroy(p->capture_stream);
@@ -1302,8 +1331,9 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     hipStream_t st = static_cast<hipStream_t>(stream);
     // back-pressure without touching the device: wait (host only) while every mailbox slot is taken by a
     // step that has not finished yet
-    volatile uint32_t *done = &p->mailbox->completed;
-    while ((uint32_t)(p->issued - *done) >= (uint32_t)kMailboxSlots - 1u) std::this_thread::yield();
+    if ((uint32_t)(p->issued - p->mailbox->completed) >= (uint32_t)kMailboxSlots - 1u &&
+        !wait_completed(p, p->issued - ((uint32_t)kMailboxSlots - 2u), kHostWaitSeconds))
+        return fail(ZG_ESTATE, "the device finished no step of this plan for 30 s while 255 are queued; nothing was enqueued");
     const uint32_t slot = p->issued % kMailboxSlots;
     p->mailbox->slot[slot].seeds = reinterpret_cast<unsigned long long>(d_seeds);
     p->mailbox->slot[slot].key = rng_key;
@@ -1318,8 +1348,42 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
         hipError_t e = hipGraphLaunch(p->graph_exec, st);
         if (e != hipSuccess) rc = fail(ZG_EHIP, std::string("hipGraphLaunch: ") + hipGetErrorString(e));
     }
-    if (rc != ZG_OK) p->issued -= 1; // nothing was enqueued: the slot is free again
+    if (rc != ZG_OK) {
+        p->issued -= 1; // nothing was enqueued: the slot is free again
+    } else {
+        p->last_stream = st;
+        p->stepped = true;
+    }
     return rc;
+}
+
+int zg_pilot_update(const zg_plan_t *p, int64_t *largest, void *stream)
+{
+    if (!p || !largest) return fail(ZG_EINVAL, "null argument");
+    uint32_t n_exact[ZG_MAX_HOPS + 1];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ZG_HIP(hipMemcpyAsync(n_exact, p->drmb()->n_exact, sizeof(n_exact), hipMemcpyDeviceToHost, st));
+    ZG_HIP(hipStreamSynchronize(st));
+    for (int h = 0; h <= p->lay.num_hops; ++h) largest[h] = std::max<int64_t>(largest[h], (int64_t)n_exact[h]);
+    return ZG_OK;
+}
+
+#ifndef ZG_BUILD_ID
+#define ZG_BUILD_ID "unknown"
+#endif
+const char *zg_build_id(void) { return ZG_BUILD_ID; }
+
+int zg_calibration_copy(const void *d_src, void *d_dst, size_t bytes, void *stream)
+{
+    if (!d_src || !d_dst || bytes == 0 || (bytes & 15u) || (reinterpret_cast<uintptr_t>(d_src) & 15u) ||
+        (reinterpret_cast<uintptr_t>(d_dst) & 15u))
+        return fail(ZG_EINVAL, "zg_calibration_copy: pointers and size must be non-null multiples of 16");
+    const size_t n = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n + kBlock - 1) / kBlock, 256u * 64u);
+    hipLaunchKernelGGL(k_calibrate_copy, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(d_src), static_cast<uint4 *>(d_dst), n);
+    ZG_HIP(hipGetLastError());
+    return ZG_OK;
 }
 
 int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch, int32_t with_replacement,

@@ -2,7 +2,6 @@
 // (paper section 4.3, Lemma 1, appendix A) and the fixed buffer layout / launch caps of a plan.
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <map>
@@ -128,7 +127,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     if (feat_dim < 0 || feat_dim > 32768) return fail(ZG_EINVAL, "feat_dim must be in 0..32768");
     for (int h = 0; h < num_hops; ++h)
         if (fanouts[h] < 1 || fanouts[h] > ZG_MAX_FANOUT) return fail(ZG_EINVAL, "fanout must be in 1..ZG_MAX_FANOUT");
-    if (env->mode < ZG_ENV_MAX || env->mode > ZG_ENV_EXPLICIT) return fail(ZG_EINVAL, "unknown envelope mode");
+    if (env->mode < ZG_ENV_MAX || env->mode > ZG_ENV_GRAPH) return fail(ZG_EINVAL, "unknown envelope mode");
     const bool replace = (env->flags & ZG_PLAN_REPLACE) != 0;
     const int64_t V = g->num_nodes;
 
@@ -153,9 +152,9 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     const double margin = env->margin >= 0 ? env->margin : 0.20;
     if (!(conf > 0.0 && conf < 1.0)) return fail(ZG_EINVAL, "confidence must be in (0,1)");
     pi.z = zg_normal_quantile(std::pow(conf, 1.0 / (double)iters));
-    for (int h = 0; h <= num_hops; ++h) {
-        pi.model_mean[h] = mean[h];
-        pi.model_sigma[h] = sigma[h];
+    for (int h = 0; h <= num_hops; ++h) { // reported: the statistics the caps were (or would be) derived from
+        pi.model_mean[h] = env->mode == ZG_ENV_GRAPH && h > 0 ? env->model_mean[h] : mean[h];
+        pi.model_sigma[h] = env->mode == ZG_ENV_GRAPH && h > 0 ? env->model_sigma[h] : sigma[h];
     }
 
     auto caps_for = [&](int mode, int64_t *node_cap) -> int {
@@ -163,11 +162,16 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         for (int h = 0; h < num_hops; ++h) {
             const int64_t worst = std::min<int64_t>(V, sat_mul_add(node_cap[h], fanouts[h]));
             int64_t want = worst;
-            if (mode == ZG_ENV_MODEL) {
-                if (g->degrees.empty()) return fail(ZG_ESTATE, "graph handle has no degree statistics");
-                const double a = (1.0 + margin) * mean[h + 1];
-                const double b = mean[h + 1] + pi.z * sigma[h + 1];
-                want = (int64_t)std::ceil(std::max(a, b));
+            if (mode == ZG_ENV_MODEL || mode == ZG_ENV_GRAPH) {
+                // section 4.3 / Lemma 1: head-room over the model mean, never less than the z-sigma band; the
+                // statistics come from the degree histogram (lemma as printed) or from the caller (graph-aware model)
+                if (mode == ZG_ENV_MODEL && g->degrees.empty()) return fail(ZG_ESTATE, "graph handle has no degree statistics");
+                const double mu = mode == ZG_ENV_MODEL ? mean[h + 1] : env->model_mean[h + 1];
+                const double sg = mode == ZG_ENV_MODEL ? sigma[h + 1] : env->model_sigma[h + 1];
+                if (!(mu >= 0.0) || !(sg >= 0.0) || !std::isfinite(mu) || !std::isfinite(sg))
+                    return fail(ZG_EINVAL, "model mean / sigma must be finite and non-negative");
+                want = (int64_t)std::ceil(std::max((1.0 + margin) * mu, mu + pi.z * sg));
+                if (want < 1) want = 1;
             } else if (mode == ZG_ENV_EXPLICIT) {
                 want = env->node_caps[h + 1];
                 if (want < 1) return fail(ZG_EINVAL, "explicit node cap < 1");
@@ -182,8 +186,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     const int64_t ldx = feat_dim > 0 ? (int64_t)align_up((size_t)feat_dim, 4) : 0;
     const bool fused = (env->flags & ZG_PLAN_FUSED_INPUT) != 0;
     // tuning knob: upper bound on the tickets (workgroups taking a tile id from one atomic counter) per kernel
-    int64_t max_tickets = kMaxTickets;
-    if (const char *e = std::getenv("ZG_MAX_TICKETS")) max_tickets = std::max(1, std::atoi(e));
+    const int64_t max_tickets = env->max_tickets > 0 ? env->max_tickets : kMaxTickets;
     auto envelope_bytes_for = [&](const int64_t *node_cap) -> int64_t {
         size_t b = align_up(sizeof(Drmb), kAlign) + kGuard + align_up((size_t)kLogCapacity * ZG_LOG_STRIDE * 4, kAlign) + kGuard;
         b += align_up((size_t)node_cap[num_hops] * 4, kAlign) + kGuard;
@@ -376,6 +379,22 @@ int zg_envelope_model(const int64_t *degrees, const int64_t *counts, int64_t n_d
         }
         mean[h + 1] = std::min(V, (double)batch + mu);
         sigma[h + 1] = std::sqrt(var);
+    }
+    return ZG_OK;
+}
+
+int zg_envelope_from_pilot(const int64_t *largest, int32_t num_hops, double margin, uint32_t flags, zg_envelope *out)
+{
+    if (!largest || !out) return fail(ZG_EINVAL, "null argument");
+    if (num_hops < 1 || num_hops > ZG_MAX_HOPS) return fail(ZG_EINVAL, "num_hops must be in 1..ZG_MAX_HOPS");
+    const double m = margin >= 0 ? margin : 0.20;
+    std::memset(out, 0, sizeof(*out));
+    out->mode = ZG_ENV_EXPLICIT;
+    out->flags = flags;
+    out->margin = m;
+    for (int h = 1; h <= num_hops; ++h) {
+        if (largest[h] < 0) return fail(ZG_EINVAL, "negative pilot size");
+        out->node_caps[h] = std::max<int64_t>(1, (int64_t)std::ceil((1.0 + m) * (double)largest[h]));
     }
     return ZG_OK;
 }

@@ -359,9 +359,10 @@ class Config:
 
 CONFIGS: Dict[str, Config] = {
     "tiny": Config("tiny", "rmat", 10_000, 150_000, torch.int32, 32, 64, (5, 5), 1, exact_edges=100_000),
-    "medium_dense": Config("medium_dense", "rmat", 250_000, 100_000_000, torch.int64, 600, 1024, (25, 10), 100),
-    "large_sparse": Config("large_sparse", "rmat", 2_400_000, 120_000_000, torch.int64, 100, 1024, (15, 10, 5), 200,
-                           pool_size=204_800),
+    "medium_dense": Config("medium_dense", "rmat", 250_000, 150_000_000, torch.int64, 600, 1024, (25, 10), 100,
+                           exact_edges=100_000_000),
+    "large_sparse": Config("large_sparse", "rmat", 2_400_000, 180_000_000, torch.int64, 100, 1024, (15, 10, 5), 200,
+                           exact_edges=120_000_000, pool_size=204_800),
     "very_large": Config("very_large", "rmat", 110_000_000, 1_600_000_000, torch.int64, 128, 4096, (15, 10, 5), 100),
     "envelope_stress": Config("envelope_stress", "chung_lu", 1_000_000, 50_000_000, torch.int64, 256, 4096, (25, 10),
                               500, hub_prob=0.10,

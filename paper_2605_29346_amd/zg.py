@@ -18,7 +18,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 I32, I64 = 0, 1
 GRAPH_VALIDATE = 1
 PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN, PLAN_FUSED_INPUT, PLAN_AUTO_FALLBACK = 1, 2, 4, 8, 16
-ENV_MAX, ENV_MODEL, ENV_EXPLICIT = 0, 1, 2
+ENV_MAX, ENV_MODEL, ENV_EXPLICIT, ENV_GRAPH = 0, 1, 2, 3
 FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
 
 
@@ -32,12 +32,15 @@ EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_s
            "zg_graph_degree_histogram", "zg_normal_quantile", "zg_envelope_model", "zg_plan_query", "zg_plan",
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
            "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
-           "zg_step_status", "zg_envelope_model_graph"]
+           "zg_step_status", "zg_envelope_model_graph", "zg_envelope_from_pilot", "zg_pilot_update", "zg_build_id",
+           "zg_calibration_copy"]
 
 
 class Envelope(C.Structure):
     _fields_ = [("mode", C.c_int32), ("flags", C.c_uint32), ("margin", C.c_double), ("confidence", C.c_double),
-                ("iterations", C.c_int64), ("node_caps", C.c_int64 * (MAX_HOPS + 1))]
+                ("iterations", C.c_int64), ("node_caps", C.c_int64 * (MAX_HOPS + 1)),
+                ("model_mean", C.c_double * (MAX_HOPS + 1)), ("model_sigma", C.c_double * (MAX_HOPS + 1)),
+                ("max_tickets", C.c_int32), ("reserved", C.c_int32)]
 
 
 class PlanInfo(C.Structure):
@@ -69,13 +72,22 @@ _lib = None
 
 
 def lib() -> C.CDLL:
-    """The loaded C-ABI library; raises if it has not been built (python -m paper_2605_29346_amd.build)."""
+    """The loaded C-ABI library.  A library that is missing, or was built from other sources than the ones beside it,
+    is (re)built when hipcc is there; otherwise this raises: there is no fallback path."""
     global _lib
     if _lib is None:
+        from . import build as _build
+        _build.ensure_current()
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: build it first (__graft_entry__.build()); "
                                "there is no fallback path")
         L = C.CDLL(_LIB_PATH)
+        L.zg_build_id.restype = C.c_char_p
+        L.zg_build_id.argtypes = []
+        want = _build.source_id()
+        if want is not None and L.zg_build_id().decode() != want:
+            raise RuntimeError(f"{_LIB_PATH} was built from other sources ({L.zg_build_id().decode()} != {want}) and "
+                               "hipcc is not available to rebuild it")
         vp, i32, i64, u32, u64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_double
         P = C.POINTER
         L.zg_strerror.restype = C.c_char_p
@@ -103,8 +115,11 @@ def lib() -> C.CDLL:
         L.zg_plan_outputs_safe.argtypes = [vp, P(Outputs)]
         L.zg_step_status.argtypes = [vp, P(u32), P(u32)]
         L.zg_envelope_model_graph.argtypes = [vp, P(i32), i32, i32, i32, vp, vp, C.c_size_t, vp, P(dbl), P(dbl)]
+        L.zg_envelope_from_pilot.argtypes = [P(i64), i32, dbl, u32, P(Envelope)]
+        L.zg_pilot_update.argtypes = [vp, P(i64), vp]
+        L.zg_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
         for name in EXPORTS:
-            if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile"):
+            if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile", "zg_build_id"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -141,12 +156,18 @@ def envelope_model(degrees: Sequence[int], counts: Sequence[int], fanouts: Seque
 
 
 def make_envelope(mode: int = ENV_MAX, *, flags: int = 0, margin: float = -1.0, confidence: float = 0.0,
-                  iterations: int = 0, node_caps: Optional[Sequence[int]] = None) -> Envelope:
+                  iterations: int = 0, node_caps: Optional[Sequence[int]] = None, model_mean: Optional[Sequence[float]] = None,
+                  model_sigma: Optional[Sequence[float]] = None, max_tickets: int = 0) -> Envelope:
     e = Envelope()
     e.mode, e.flags, e.margin, e.confidence, e.iterations = mode, flags, margin, confidence, iterations
+    e.max_tickets = max_tickets
     if node_caps is not None:
         for h, c in enumerate(node_caps):
             e.node_caps[h] = int(c)
+    for dst, src in ((e.model_mean, model_mean), (e.model_sigma, model_sigma)):
+        if src is not None:
+            for h, x in enumerate(src):
+                dst[h] = float(x)
     return e
 
 
@@ -200,32 +221,37 @@ def graph_model(graph: "Graph", fanouts: Sequence[int], batch: int, *, with_repl
 
 def graph_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, *, margin: float = 0.20, confidence: float = 0.999,
                    iterations: int = 100_000, flags: int = 0, seed_prob=None) -> Envelope:
-    """Explicit caps from the graph-aware model: max((1 + margin) mean, mean + z sigma) per hop, z as in the lemma."""
+    """A ZG_ENV_GRAPH request: mean and sigma from the graph-aware size model; the library's planner turns them into
+    caps (the lemma's margin / z-sigma formula)."""
     mean, sigma = graph_model(graph, fanouts, batch, with_replacement=bool(flags & PLAN_REPLACE), seed_prob=seed_prob)
-    z = normal_quantile(confidence ** (1.0 / iterations))
-    caps = [0] + [int(max((1.0 + margin) * m, m + z * s)) + 1 for m, s in zip(mean[1:], sigma[1:])]
-    return make_envelope(ENV_EXPLICIT, flags=flags, node_caps=caps)
+    return make_envelope(ENV_GRAPH, flags=flags, margin=margin, confidence=confidence, iterations=iterations,
+                         model_mean=mean, model_sigma=sigma)
 
 
 def pilot_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, seed_batches, keys, *, margin: float = 0.20,
                    flags: int = 0) -> Envelope:
-    """Plan-time pilot (the paper's warm-up iterations): run the given mini-batches once on a worst-case plan,
-    take the largest realised n_h per hop and return an explicit envelope with `margin` head-room over it.
-    Every step runs in the library; this only reads the realised sizes back."""
-    import torch
+    """Plan-time pilot (the paper's warm-up iterations): run the given mini-batches once on a worst-case plan; the
+    library tracks the largest realised n_h per hop (zg_pilot_update) and turns it into an explicit envelope with
+    `margin` head-room (zg_envelope_from_pilot)."""
     H = len(fanouts)
     plan = Plan(graph, fanouts, batch, make_envelope(ENV_MAX, flags=flags & PLAN_REPLACE))
-    largest = [0] * (H + 1)
+    largest = (C.c_int64 * (MAX_HOPS + 1))()
     try:
         for seeds, key in zip(seed_batches, keys):
             plan.step(seeds, key)
-            torch.cuda.synchronize()
-            n = plan.view_counts()[0].cpu().tolist()
-            largest = [max(a, int(b)) for a, b in zip(largest, n)]
+            _check(lib().zg_pilot_update(plan._h, largest, _stream_ptr(None)))
     finally:
         plan.close()
-    caps = [0] + [int(x * (1.0 + margin)) + 1 for x in largest[1:]]
-    return make_envelope(ENV_EXPLICIT, flags=flags, node_caps=caps)
+    env = Envelope()
+    _check(lib().zg_envelope_from_pilot(largest, H, margin, flags, C.byref(env)))
+    return env
+
+
+def calibration_copy(src, dst, stream=None) -> None:
+    """dst = src as one plain streaming kernel of the library (reads and writes src.numel() * itemsize bytes)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().zg_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)))
 
 
 class Graph:

@@ -11,10 +11,10 @@ if ROOT not in sys.path:
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
     config.addinivalue_line("markers", "slow: long-running full-size case")
-    # the tests load the library that is built; only if there is none do they build it (hipcc cross-compiles without a GPU)
+    # the tests load the library that is built; it is rebuilt only if it is missing or was built from other sources
+    # than the ones in the tree (hipcc cross-compiles without a GPU)
     from paper_2605_29346_amd import build as zg_build
-    if not os.path.exists(zg_build.LIB):
-        zg_build.build(force=True)
+    zg_build.ensure_current()
 
 
 @pytest.fixture(scope="session")

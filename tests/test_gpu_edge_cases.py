@@ -1,6 +1,6 @@
 """GPU parity on the degenerate and extreme shapes of the method: no edges at all, a single seed, every
 vertex a seed, the maximum number of hops, fanout 64 on a six-figure degree, vertex counts that are not a
-multiple of 32, and every tile-size variant of the chained-scan kernels (forced through ZG_MAX_TICKETS)."""
+multiple of 32, and every tile-size variant of the chained-scan kernels (forced through the envelope's max_tickets knob)."""
 import os
 
 import numpy as np
@@ -90,20 +90,17 @@ def test_fanout_64_on_a_huge_row(oracle):
 @pytest.mark.parametrize("max_tickets", [1, 2, 4, 16, 64])
 def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
     # tiny ticket budgets force several tiles per sampling ticket and 2..16 rounds per compaction tile
-    os.environ["ZG_MAX_TICKETS"] = str(max_tickets)
-    try:
-        g = W.rmat_graph(600_000, 3_000_000, 17)
-        feat = W.feature_table(600_000, 4, 2)
-        og = to_host_graph(oracle, g)
-        pool = W.SeedPool(g, 3000, 5)
-        plan = None
-        for s in range(2):
-            plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (6, 5, 3), 40 + s, plan=plan, og=og)
-        info = plan.info
-        assert info.grid_compact <= max(max_tickets, (600_000 // 32 + 16383) // 16384)
-        assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 4)))  # at most 4 tiles of 256 vertices per ticket
-    finally:
-        del os.environ["ZG_MAX_TICKETS"]
+    g = W.rmat_graph(600_000, 3_000_000, 17)
+    feat = W.feature_table(600_000, 4, 2)
+    og = to_host_graph(oracle, g)
+    pool = W.SeedPool(g, 3000, 5)
+    plan = None
+    for s in range(2):
+        plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (6, 5, 3), 40 + s, plan=plan, og=og,
+                                         env=zg.make_envelope(zg.ENV_MAX, max_tickets=max_tickets))
+    info = plan.info
+    assert info.grid_compact <= max(max_tickets, (600_000 // 32 + 16383) // 16384)
+    assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 4)))  # at most 4 tiles of 256 vertices per ticket
 
 
 def test_randomised_configurations(oracle):

@@ -184,3 +184,76 @@ def test_graph_aware_model_rejects_bad_arguments_before_touching_a_device():
     assert L.zg_envelope_model_graph(g._h, fan, 2, 100, 0, None, 256, 10**9, None, mean, sigma) == zg.ESTATE
     assert L.zg_envelope_model_graph(None, fan, 2, 100, 0, None, 256, 10**9, None, mean, sigma) == zg.EINVAL
     assert L.zg_envelope_model_graph(g._h, fan, 2, 100, 0, None, None, 10**9, None, mean, sigma) == zg.EINVAL
+
+
+def test_graph_mode_applies_the_lemma_cap_formula_to_the_callers_statistics():
+    # ZG_ENV_GRAPH: caps = ceil(max((1 + margin) mean, mean + z sigma)) from the mean / sigma handed in (the output of
+    # the graph-aware size model), clamped by the worst case and never below the previous hop's cap
+    g = _stats_graph()
+    mean, sigma = [0.0, 431.25, 1800.5], [0.0, 5.0, 400.0]
+    env = zg.make_envelope(zg.ENV_GRAPH, margin=0.1, confidence=0.999, iterations=1000, model_mean=mean, model_sigma=sigma)
+    info = g.plan_query((5, 4), 100, env, feat_dim=8)
+    z = zg.normal_quantile(0.999 ** (1 / 1000))
+    assert abs(info.z - z) < 1e-12
+    assert info.node_cap[1] == math.ceil(1.1 * 431.25)                      # the margin term wins: 474.375 -> 475
+    assert info.node_cap[2] == min(info.node_cap[1] * 5, math.ceil(1800.5 + z * 400.0))  # the z-sigma band wins
+    assert [info.model_mean[h] for h in (1, 2)] == mean[1:] and [info.model_sigma[h] for h in (1, 2)] == sigma[1:]
+    # defaults: margin 0.20, confidence 0.9999 over 1000 iterations
+    info = g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_GRAPH, model_mean=mean, model_sigma=[0, 0, 0]), feat_dim=8)
+    assert list(info.node_cap[1:3]) == [math.ceil(1.2 * 431.25), math.ceil(1.2 * 1800.5)]
+    # a statistics-only handle is enough (the statistics are the caller's); nonsense is refused
+    for bad in ([0.0, float("nan"), 1.0], [0.0, -3.0, 1.0], [0.0, float("inf"), 1.0]):
+        with pytest.raises(zg.ZgError):
+            g.plan_query((5, 4), 100, zg.make_envelope(zg.ENV_GRAPH, model_mean=bad, model_sigma=sigma))
+    with pytest.raises(zg.ZgError):
+        g.plan_query((5, 4), 100, zg.make_envelope(4))
+
+
+def test_pilot_helper_adds_the_margin_to_the_largest_sizes():
+    L = zg.lib()
+    largest = (ctypes.c_int64 * 9)(999, 1000, 4321, 10)
+    env = zg.Envelope()
+    assert L.zg_envelope_from_pilot(largest, 3, 0.25, zg.PLAN_REPLACE, ctypes.byref(env)) == zg.OK
+    assert env.mode == zg.ENV_EXPLICIT and env.flags == zg.PLAN_REPLACE
+    assert list(env.node_caps[:4]) == [0, 1250, math.ceil(1.25 * 4321), 13]
+    assert L.zg_envelope_from_pilot(largest, 3, -1.0, 0, ctypes.byref(env)) == zg.OK   # default margin 20 %
+    assert list(env.node_caps[1:4]) == [1200, math.ceil(1.2 * 4321), 12]
+    assert L.zg_envelope_from_pilot(largest, 0, 0.2, 0, ctypes.byref(env)) == zg.EINVAL
+    assert L.zg_envelope_from_pilot(None, 3, 0.2, 0, ctypes.byref(env)) == zg.EINVAL
+    largest[2] = -1
+    assert L.zg_envelope_from_pilot(largest, 3, 0.2, 0, ctypes.byref(env)) == zg.EINVAL
+
+
+def test_ticket_budget_is_an_envelope_field_not_an_environment_variable():
+    g = _stats_graph()
+    wide = g.plan_query((5, 4, 3), 2000, zg.make_envelope(zg.ENV_MAX))
+    os.environ["ZG_MAX_TICKETS"] = "1"
+    try:
+        assert list(g.plan_query((5, 4, 3), 2000, zg.make_envelope(zg.ENV_MAX)).grid_sample[:3]) == list(wide.grid_sample[:3])
+    finally:
+        del os.environ["ZG_MAX_TICKETS"]
+    narrow = g.plan_query((5, 4, 3), 2000, zg.make_envelope(zg.ENV_MAX, max_tickets=2))
+    assert narrow.grid_sample[2] < wide.grid_sample[2] and list(narrow.node_cap[:4]) == list(wide.node_cap[:4])
+
+
+def test_the_binding_holds_none_of_the_envelope_arithmetic():
+    # caps are computed behind the C ABI: the binding only forwards numbers
+    src = open(os.path.join(ROOT, "paper_2605_29346_amd", "zg.py")).read()
+    for token in ("max(", "ceil(", "sigma *", "* sigma", "1.0 + margin", "1 + margin"):
+        assert token not in src, token
+
+
+def test_every_device_flag_reaches_the_per_step_word():
+    # a kernel that raises a ZG_FLAG_* bit in the sticky word raises it in the per-step word as well (that is what the
+    # step log, the mailbox status and zg_step_status report): every atomicOr on `flags` is followed by its twin
+    lines = open(os.path.join(ROOT, "paper_2605_29346_amd", "csrc", "zg_device.hip")).read().splitlines()
+    sticky = [i for i, l in enumerate(lines) if "atomicOr(&" in l and "->flags," in l]
+    assert len(sticky) >= 4
+    for i in sticky:
+        nxt = lines[i + 1]
+        assert "->step_flags," in nxt and nxt.split("step_flags,")[1] == lines[i].split("flags,")[1], lines[i]
+
+
+def test_build_id_names_the_sources_in_the_tree():
+    from paper_2605_29346_amd import build as zg_build
+    assert zg.lib().zg_build_id().decode() == zg_build.source_id()
