@@ -364,6 +364,29 @@ def test_fused_input_only_materialises_the_frontier_rows(oracle, dim):
     assert np.array_equal(both[:, half: half + dim].view(np.uint32), res.agg.view(np.uint32))
 
 
+def test_host_back_pressure_when_more_steps_are_queued_than_the_mailbox_holds(oracle):
+    # 700 steps issued on one plan with no sync: the 256-slot ring of per-step inputs fills up and zg_step waits on the
+    # host for the device-published counter (it never synchronises with the device); every step's sizes must still be
+    # right, i.e. no slot was overwritten before its step had read it
+    g = W.rmat_graph(30_000, 600_000, 21)
+    og = to_host_graph(oracle, g)
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    pool = W.SeedPool(g, 128, 2)
+    plan = zg.Plan(dg, (8, 4), 128, zg.make_envelope(zg.ENV_MAX))
+    steps = 700
+    batches = [pool.batch_for(s).cuda() for s in range(steps)]
+    torch.cuda.synchronize()
+    for s in range(steps):
+        plan.step(batches[s], 9000 + s)
+    torch.cuda.synchronize()
+    assert plan.step_status() == (steps, 0)
+    log = plan.view_log().cpu().numpy()
+    for s in range(steps):
+        ref = og.sample_blocks(batches[s].cpu().numpy(), (8, 4), 9000 + s)
+        rec = log[s % log.shape[0]]
+        assert rec[0] == s and rec[1] == 0 and list(rec[2:5]) == ref.n and list(rec[5:7]) == ref.E, f"step {s}"
+
+
 def test_pilot_envelope_is_tight_and_does_not_overflow(oracle):
     g = W.rmat_graph(50_000, 1_000_000, 12)
     dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
