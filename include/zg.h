@@ -199,6 +199,21 @@ int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t
                             int32_t with_replacement, const float *d_seed_prob, void *d_temp, size_t temp_bytes,
                             void *stream, double *mean, double *sigma);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): zg_envelope_model_graph without the caller's d_temp.  Its scratch is a static device array of
+ * the library (12 bytes per vertex for ZG_STATIC_MODEL_MAX_NODES vertices, 12.6 MB, one copy per GPU, held until
+ * the process ends), so graphs with more vertices are refused (ZG_EINVAL).  The call allocates nothing, copies
+ * nothing and never synchronises: it enqueues 2 + 2 * num_hops + 1 kernels on `stream` (no memset node) and leaves
+ * the result on the device, d_mean_sigma[0..H] = mean[0..H] and d_mean_sigma[H+1..2H+1] = sigma[0..H] (device
+ * memory, 2 * (num_hops + 1) doubles, 8-byte aligned, valid once `stream` reaches this point).  Every call on a
+ * GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race and give undefined
+ * results; calls in stream order are fine, each starts from a clean state.  Same values as
+ * zg_envelope_model_graph (integer sums).  Errors: ZG_EINVAL (arguments, too many vertices), ZG_ESTATE
+ * (statistics-only handle, other device), ZG_EHIP. */
+#define ZG_STATIC_MODEL_MAX_NODES (1 << 20)
+int zg_envelope_model_graph_static(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+                                   int32_t with_replacement, const float *d_seed_prob, void *stream, double *d_mean_sigma);
+
 /* Envelope from a pilot run (section 4.4 warm-up iterations; appendix B observes realised sizes within a few
  * percent of each other): `largest[h]`, h = 1..H, is the largest n_h seen over the pilot's mini-batches ([0]
  * ignored).  Fills *out as a ZG_ENV_EXPLICIT request with node_caps[h] = ceil((1 + margin) * largest[h]),

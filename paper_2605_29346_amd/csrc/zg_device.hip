@@ -18,6 +18,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 
@@ -852,6 +853,26 @@ __global__ __launch_bounds__(kBlock) void k_model_update(float *q, unsigned long
     }
 }
 
+// results of the size model left on the device: out[0..H] = mean, out[H+1..2H+1] = sigma (sums: per hop {sum q, sum q(1-q)} in 2^-32 units)
+__global__ void k_model_finish(const unsigned long long *sums, int32_t num_hops, int32_t batch, double *out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    out[0] = (double)batch;
+    out[num_hops + 1] = 0.0;
+    for (int h = 0; h < num_hops; ++h) {
+        out[h + 1] = (double)sums[2 * h] / kFix;
+        out[num_hops + 1 + h + 1] = sqrt((double)sums[2 * h + 1] / kFix);
+    }
+}
+
+// Scratch of zg_envelope_model_graph_static: the per-vertex log-sums (8 bytes) and probabilities (4 bytes) for up to
+// ZG_STATIC_MODEL_MAX_NODES vertices plus the per-hop sums.  One copy per GPU, held until the process ends; host code
+// never uses the array's name as an address, only what hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticEllBytes = (size_t)ZG_STATIC_MODEL_MAX_NODES * 8;
+constexpr size_t kStaticQBytes = (size_t)ZG_STATIC_MODEL_MAX_NODES * 4;
+constexpr size_t kStaticSumsBytes = 2 * ZG_MAX_HOPS * 8;
+static __device__ __align__(256) unsigned char scratch[kStaticEllBytes + kStaticQBytes + kStaticSumsBytes];
+
 #define ZG_HIP(call)                                                                                         \
     do {                                                                                                     \
         hipError_t e_ = (call);                                                                              \
@@ -1433,6 +1454,70 @@ int zg_envelope_model_graph(const zg_graph_t *g, const int32_t *fanouts, int32_t
         mean[h + 1] = (double)host[0] / kFix;
         sigma[h + 1] = std::sqrt((double)host[1] / kFix);
     }
+    return ZG_OK;
+}
+
+// device address of this GPU's copy of `scratch`, looked up once per device with that device current
+static int static_scratch(int device, unsigned char **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static unsigned char *ptr[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices) return fail(ZG_EINVAL, "device index out of range");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[device]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(zg::scratch));
+        if (e != hipSuccess || !p) return fail(ZG_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        ptr[device] = static_cast<unsigned char *>(p);
+    }
+    *out = ptr[device];
+    return ZG_OK;
+}
+
+int zg_envelope_model_graph_static(const zg_graph_t *g, const int32_t *fanouts, int32_t num_hops, int32_t batch,
+                                   int32_t with_replacement, const float *d_seed_prob, void *stream, double *d_mean_sigma)
+{
+    if (!g || !fanouts || !d_mean_sigma) return fail(ZG_EINVAL, "null argument");
+    if (g->stats_only) return fail(ZG_ESTATE, "the graph-aware model needs a graph handle with device arrays");
+    if (num_hops < 1 || num_hops > ZG_MAX_HOPS) return fail(ZG_EINVAL, "num_hops must be in 1..ZG_MAX_HOPS");
+    if (batch < 1 || batch > g->num_nodes) return fail(ZG_EINVAL, "batch must be in 1..num_nodes");
+    for (int h = 0; h < num_hops; ++h)
+        if (fanouts[h] < 1 || fanouts[h] > ZG_MAX_FANOUT) return fail(ZG_EINVAL, "fanout must be in 1..ZG_MAX_FANOUT");
+    const int64_t n = g->num_nodes;
+    if (n > (int64_t)ZG_STATIC_MODEL_MAX_NODES)
+        return fail(ZG_EINVAL, "zg_envelope_model_graph_static: the graph has more vertices than ZG_STATIC_MODEL_MAX_NODES, the "
+                               "capacity of the library's static scratch; use zg_envelope_model_graph with a caller buffer");
+    if ((reinterpret_cast<uintptr_t>(d_mean_sigma) & 7u) != 0) return fail(ZG_EINVAL, "d_mean_sigma must be 8-byte aligned");
+    int device = -1;
+    ZG_HIP(hipGetDevice(&device));
+    if (device != g->device) return fail(ZG_ESTATE, "current device differs from the graph's device");
+    unsigned char *base = nullptr;
+    int rc = static_scratch(device, &base);
+    if (rc != ZG_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned long long *ell = reinterpret_cast<unsigned long long *>(base);
+    float *q = reinterpret_cast<float *>(base + kStaticEllBytes);
+    unsigned long long *sums = reinterpret_cast<unsigned long long *>(base + kStaticEllBytes + kStaticQBytes);
+    const int grid = (int)std::min<int64_t>(1 << 16, (n + kBlock - 1) / kBlock);
+    const int grid_push = (int)std::min<int64_t>(1 << 16, (n + (kBlock / 64) - 1) / (kBlock / 64));
+    // the array keeps the last call's contents: the per-hop sums restart at zero here (a fill kernel, not a memset
+    // node, so that the sequence may be captured), q and ell are overwritten for the first n vertices by the first kernel
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t *>(sums), 0u, (size_t)(4 * ZG_MAX_HOPS));
+    hipLaunchKernelGGL(k_model_init, dim3(grid), dim3(kBlock), 0, st, q, ell, d_seed_prob, (float)((double)batch / (double)n), n);
+    ZG_HIP(hipGetLastError());
+    for (int h = 0; h < num_hops; ++h) {
+        if (g->offsets_dtype == ZG_I64)
+            hipLaunchKernelGGL(k_model_push<int64_t>, dim3(grid_push), dim3(kBlock), 0, st, (const int64_t *)g->d_offsets, g->d_indices, q,
+                               ell, n, fanouts[h], with_replacement);
+        else
+            hipLaunchKernelGGL(k_model_push<int32_t>, dim3(grid_push), dim3(kBlock), 0, st, (const int32_t *)g->d_offsets, g->d_indices, q,
+                               ell, n, fanouts[h], with_replacement);
+        hipLaunchKernelGGL(k_model_update, dim3(grid), dim3(kBlock), 0, st, q, ell, n, sums + 2 * h);
+        ZG_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_model_finish, dim3(1), dim3(64), 0, st, sums, num_hops, batch, d_mean_sigma);
+    ZG_HIP(hipGetLastError());
     return ZG_OK;
 }
 

@@ -33,7 +33,7 @@ EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_s
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
            "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
            "zg_step_status", "zg_envelope_model_graph", "zg_envelope_from_pilot", "zg_pilot_update", "zg_build_id",
-           "zg_calibration_copy"]
+           "zg_calibration_copy", "zg_envelope_model_graph_static"]
 
 
 class Envelope(C.Structure):
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
         L.zg_plan_outputs_safe.argtypes = [vp, P(Outputs)]
         L.zg_step_status.argtypes = [vp, P(u32), P(u32)]
         L.zg_envelope_model_graph.argtypes = [vp, P(i32), i32, i32, i32, vp, vp, C.c_size_t, vp, P(dbl), P(dbl)]
+        L.zg_envelope_model_graph_static.argtypes = [vp, P(i32), i32, i32, i32, vp, vp, vp]
         L.zg_envelope_from_pilot.argtypes = [P(i64), i32, dbl, u32, P(Envelope)]
         L.zg_pilot_update.argtypes = [vp, P(i64), vp]
         L.zg_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -217,6 +218,18 @@ def graph_model(graph: "Graph", fanouts: Sequence[int], batch: int, *, with_repl
     _check(lib().zg_envelope_model_graph(graph._h, f, H, batch, int(with_replacement), sp.data_ptr() if sp is not None else None,
                                          base, nbytes, _stream_ptr(stream), mean, sigma))
     return list(mean[: H + 1]), list(sigma[: H + 1])
+
+
+def graph_model_static(graph: "Graph", fanouts: Sequence[int], batch: int, out, *, with_replacement: bool = False,
+                       seed_prob=None, stream=None) -> None:
+    """The graph-aware size model on the library's static scratch: allocates nothing, does not synchronise; `out` (float64
+    CUDA tensor, 2 * (H + 1) elements) receives mean[0..H] then sigma[0..H] once the stream gets there."""
+    H = len(fanouts)
+    f = (C.c_int32 * H)(*fanouts)
+    assert out.is_cuda and out.element_size() == 8 and out.numel() >= 2 * (H + 1) and out.is_contiguous()
+    _check(lib().zg_envelope_model_graph_static(graph._h, f, H, batch, int(with_replacement),
+                                                seed_prob.data_ptr() if seed_prob is not None else None, _stream_ptr(stream),
+                                                out.data_ptr()))
 
 
 def graph_envelope(graph: "Graph", fanouts: Sequence[int], batch: int, *, margin: float = 0.20, confidence: float = 0.999,
