@@ -245,6 +245,10 @@ def main():
     ap.add_argument("--pipeline", type=int, default=4,
                     help="independent plans replayed round-robin on their own streams (consecutive mini-batches do not "
                          "depend on each other); 1 = strictly one step after the other")
+    ap.add_argument("--input-cache", default="", help="folder for the generated graph and seed batches (.npy): written when "
+                    "absent, loaded otherwise, so that a profiled run launches none of the generator's kernels")
+    ap.add_argument("--empty-features", action="store_true", help="--profile-loop only: leave the feature table uninitialised "
+                    "(memory traffic and timing do not depend on the values; results are not checked in this mode)")
     ap.add_argument("--profile-loop", action="store_true", help="only the steady-state loop (on --pipeline plans) and three "
                     "launches of the calibration copy: the program to run under rocprofv3")
     args = ap.parse_args()
@@ -267,16 +271,33 @@ def main():
     K, Wm = args.steps, args.warmup
 
     t0 = time.time()
-    g = cfg.build_graph(device=dev)
-    torch.cuda.synchronize()
-    log(f"[bench] graph {cfg.name}: |V|={g.num_nodes} |E|={g.num_edges} ({time.time() - t0:.1f}s)")
-    t0 = time.time()
-    feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device=dev)
-    pool = cfg.seed_pool(g)
-    batches = [pool.batch_for(s).contiguous() for s in range(K + Wm)]
+    cache = os.path.join(args.input_cache, f"{cfg.name}_{K + Wm}") if args.input_cache else ""
+    pool = None
+    if cache and os.path.exists(cache + "_batches.npy"):
+        g = W.Graph(0, torch.from_numpy(np.load(cache + "_offsets.npy")).to(dev), torch.from_numpy(np.load(cache + "_indices.npy")).to(dev))
+        g.num_nodes = g.offsets.numel() - 1
+        batches = list(torch.from_numpy(np.load(cache + "_batches.npy")).to(dev))
+        log(f"[bench] graph {cfg.name} and {len(batches)} seed batches loaded from {args.input_cache} ({time.time() - t0:.1f}s)")
+    else:
+        g = cfg.build_graph(device=dev)
+        pool = cfg.seed_pool(g)
+        batches = [pool.batch_for(s).contiguous() for s in range(K + Wm)]
+        torch.cuda.synchronize()
+        log(f"[bench] graph {cfg.name}: |V|={g.num_nodes} |E|={g.num_edges}, {len(batches)} seed batches ({time.time() - t0:.1f}s)")
+        if cache:
+            os.makedirs(args.input_cache, exist_ok=True)
+            np.save(cache + "_offsets.npy", g.offsets.cpu().numpy())
+            np.save(cache + "_indices.npy", g.indices.cpu().numpy())
+            np.save(cache + "_batches.npy", torch.stack(batches).cpu().numpy())
+            log(f"[bench] inputs written to {args.input_cache} ({time.time() - t0:.1f}s)")
     keys = [cfg.key_for(s) for s in range(K + Wm)]
+    t0 = time.time()
+    if args.empty_features and args.profile_loop:
+        feat = torch.empty((g.num_nodes, cfg.dim), dtype=torch.float32, device=dev)
+    else:
+        feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device=dev)
     torch.cuda.synchronize()
-    log(f"[bench] features {tuple(feat.shape)} + {len(batches)} seed batches ({time.time() - t0:.1f}s)")
+    log(f"[bench] features {tuple(feat.shape)} ({time.time() - t0:.1f}s)")
 
     dg = zg.Graph(g.offsets, g.indices)
     H = len(cfg.fanouts)
@@ -284,6 +305,7 @@ def main():
     def make_plan(mode, flags=0):
         flags |= zg.PLAN_EAGER if args.eager else 0
         if mode == "graph":
+            assert pool is not None, "--env graph needs the seed pool: do not combine it with a loaded --input-cache"
             env = zg.graph_envelope(dg, cfg.fanouts, cfg.batch, flags=flags, seed_prob=pool.seed_prob(g.num_nodes))
         else:
             env = zg.make_envelope(zg.ENV_MODEL if mode == "model" else zg.ENV_MAX, flags=flags)
