@@ -92,8 +92,9 @@ typedef struct {
     int64_t node_caps[ZG_MAX_HOPS + 1]; /* ZG_ENV_EXPLICIT: cap of n_h for h = 1..H ([0] ignored); clamped to the worst case */
     double model_mean[ZG_MAX_HOPS + 1];  /* ZG_ENV_GRAPH: mean of n_h, h = 1..H ([0] ignored) */
     double model_sigma[ZG_MAX_HOPS + 1]; /* ZG_ENV_GRAPH: sigma of n_h */
-    int32_t max_tickets; /* tuning knob, <= 0 selects 512: how many workgroups of one kernel may take a tile id from a
-                            shared atomic counter (tiles grow to stay below it).  Results do not depend on it. */
+    int32_t max_tickets; /* tuning knob, <= 0 selects 480: how many workgroups of one launch take a tile id from a shared
+                            atomic counter (tiles grow to stay below it; the default is what an MI355X holds at once).
+                            Results do not depend on it. */
     int32_t reserved;
 } zg_envelope;
 
@@ -111,8 +112,9 @@ typedef struct {
     int64_t scratch_bytes;                /* id map over |V|, bitmap, scan state */
     int64_t workspace_bytes;              /* envelope + scratch + alignment: what zg_plan needs */
     int64_t maxsg_envelope_bytes;         /* envelope_bytes if ZG_ENV_MAX had been used */
-    int32_t grid_sample[ZG_MAX_HOPS];     /* launch caps (workgroups) of the fixed launch skeleton */
-    int32_t grid_compact;
+    int32_t grid_sample[ZG_MAX_HOPS];     /* launch caps (workgroups) of the fixed launch skeleton: hop kernel launch h
+                                             (samples hop h; for h > 0 it first ranks the vertices hop h-1 discovered) */
+    int32_t grid_compact;                 /* the closing hop-kernel launch (ranks the last hop's vertices, samples nothing) */
     int32_t grid_relabel[ZG_MAX_HOPS];
     int32_t grid_gather;
     int32_t grid_aggregate;

@@ -1,9 +1,13 @@
 // HIP kernels (gfx950, wave64) and the plan / step entry points of libzg.
 //
-// One step = ingest; per hop h: {sample hop h  +  relabel the edges of hop h-1}, {compact hop h};
-// then {gather + relabel the last hop}, {aggregate + finish}: 2H+3 launches.  Work that only depends on
-// the same predecessor shares a launch (the workgroups of a launch are split by role), because at
-// mini-batch sizes a launch costs about as much as the small kernels themselves.
+// One step = H+3 launches: the hop kernel's launches 0..H, then {gather + relabel of the last hop} and
+// {aggregate + finish}.  Launch l of the hop kernel samples hop l (l < H) and, for l > 0, first ranks the vertices hop
+// l-1 discovered - they are rows of block l themselves, so ranking and sampling share their chained scans; launch
+// 0 also ingests the seeds and launch l >= 2 relabels the edges of hop l-2 (workgroups of a launch are split by role).
+// Every kernel boundary costs about as much as the small kernels themselves at mini-batch sizes, and kernels of
+// different streams do not hide it from each other, so the step is cut into as few launches as its global
+// dependencies allow: "all of hop l-1 sampled" before its vertices can be ranked, and "all vertices ranked" before
+// the features move.
 // Every kernel is launched with a grid fixed by the plan's capacity envelope, reads the true sizes
 // from the device-resident metadata buffer and lets surplus workgroups return at once (paper
 // sections 4.1-4.3).  The whole step is one hipGraph (section 4.4); the step's seeds pointer and key reach it
@@ -34,6 +38,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr uint64_t kStAggregate = 1ull << 62; // tile total published
 constexpr uint64_t kStPrefix = 2ull << 62;    // inclusive prefix published
+constexpr uint64_t kStValueMask = (1ull << 62) - 1;
 constexpr uint32_t kSpinLimit = 1u << 22;     // bounded wait: polls before giving up with ZG_FLAG_INTERNAL
 
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane)
@@ -53,6 +58,13 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
     return v;
 }
 
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, d, 64);
+    return v;
+}
+
 __device__ __forceinline__ void st_store(uint64_t *p, uint64_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -63,45 +75,57 @@ __device__ __forceinline__ uint64_t st_load(uint64_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Single-pass chained scan across workgroups: tile `tile` (tickets are handed out in start order, so
-// every predecessor is already running) publishes its total, then wave 0 walks back over the
-// predecessors' status words, 64 at a time, until it meets a published inclusive prefix.  A status word
-// carries state and value together, so one relaxed 64-bit access is enough.  The wait is bounded.
-__device__ uint32_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, uint32_t total, Drmb *d, int lane)
+// Single-pass chained scan across workgroups: ticket `tile` (tickets are handed out in start order, so every
+// predecessor is already running) publishes its total and then looks back over the predecessors' status words until
+// it meets a published inclusive prefix.  A status word carries state (2 bits) and value (62 bits) together, so one
+// relaxed 64-bit access is enough.  One wavefront looks back, 64 predecessors per round (sharing a look-back among
+// eight wavefronts so that one round covers 512 predecessors was measured: no faster - the wait is for the
+// predecessors to publish, not for the rounds - and eight times the polling).  The wait is bounded; when it runs out
+// the step is flagged invalid (sticky and per-step word) and a clamped value is used.
+__device__ __forceinline__ uint64_t lookback_round(uint64_t *status, int64_t base, Drmb *d, int lane, bool &found)
+{
+    // the 64 status words base, base-1, .. base-63 (indices below zero count as an inclusive prefix of zero)
+    const int64_t idx = base - lane;
+    uint64_t st;
+    uint32_t spins = 0;
+    for (;;) {
+        st = idx >= 0 ? st_load(&status[idx]) : kStPrefix;
+        const bool invalid = (st >> 62) == 0;
+        if (!__any(invalid)) break;
+        if (++spins > kSpinLimit) {
+            if (lane == 0) { // the step's outputs are invalid: both the sticky and the per-step word say so
+                atomicOr(&d->flags, ZG_FLAG_INTERNAL);
+                atomicOr(&d->step_flags, ZG_FLAG_INTERNAL);
+            }
+            if (invalid) st = kStAggregate;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    const unsigned long long pm = __ballot((st >> 62) == 2);
+    const uint64_t val = st & kStValueMask;
+    found = pm != 0ull;
+    if (pm) {
+        const int first = __ffsll((long long)pm) - 1;
+        return wave_sum64(lane <= first ? val : 0ull);
+    }
+    return wave_sum64(val);
+}
+
+// all 64 lanes of one wavefront: publish, then look back 64 at a time
+__device__ uint64_t chained_exclusive_prefix(uint64_t *status, uint32_t tile, uint64_t total, Drmb *d, int lane)
 {
     if (lane == 0) st_store(&status[tile], (tile == 0 ? kStPrefix : kStAggregate) | total);
-    uint32_t excl = 0;
+    uint64_t excl = 0;
     if (tile > 0) {
         int64_t base = (int64_t)tile - 1;
-        uint32_t spins = 0;
         for (;;) {
-            const int64_t idx = base - lane;
-            uint64_t st;
-            for (;;) {
-                st = idx >= 0 ? st_load(&status[idx]) : kStPrefix;
-                const bool invalid = (st >> 62) == 0;
-                if (!__any(invalid)) break;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) { // the step's outputs are invalid: both the sticky and the per-step word say so
-                        atomicOr(&d->flags, ZG_FLAG_INTERNAL);
-                        atomicOr(&d->step_flags, ZG_FLAG_INTERNAL);
-                    }
-                    if (invalid) st = kStAggregate;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(2);
-            }
-            const unsigned long long pm = __ballot((st >> 62) == 2);
-            const uint32_t val = (uint32_t)st;
-            if (pm) {
-                const int first = __ffsll((long long)pm) - 1;
-                excl += wave_sum(lane <= first ? val : 0u);
-                break;
-            }
-            excl += wave_sum(val);
+            bool found;
+            excl += lookback_round(status, base, d, lane, found);
+            if (found) break;
             base -= 64;
         }
-        if (lane == 0) st_store(&status[tile], kStPrefix | (uint64_t)(excl + total));
+        if (lane == 0) st_store(&status[tile], kStPrefix | ((excl + total) & kStValueMask));
     }
     return excl;
 }
@@ -145,7 +169,8 @@ struct WaveGroup {
 // `completed`, which the host checks (no device synchronisation) before it reuses a slot.
 struct Mailbox {
     uint32_t completed;
-    uint32_t pad[3];
+    uint32_t issued; // steps the host has handed over so far (their slots are filled)
+    uint32_t pad[2];
     uint32_t status[kMailboxSlots]; // ZG_FLAG_* bits raised by the step that used the slot
     struct {
         unsigned long long seeds; // device address of the step's seed ids
@@ -170,26 +195,34 @@ struct IngestArgs {
     int32_t *S;
     int32_t *local_id;
     uint32_t *seen;
-    uint64_t *status;
-    uint64_t status_words;
     uint32_t batch;
     uint32_t num_nodes;
+    uint32_t blocks; // workgroups given to this role (0: role absent)
 };
 
-// Step entry: seeds -> D_0 (caller's order), their local ids and "seen" bits; step key and counters ->
-// metadata buffer; scan state cleared.  Out-of-range seeds are replaced by -1 (a vertex with no
-// neighbors); a seed whose "seen" bit is already set is a duplicate.
-__global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
+// The step's (seeds pointer, key).  A read of the pinned-host mailbox costs the device several microseconds, at the head
+// of the step's dependency chain; when the host runs ahead of the device - the normal case in a training loop - the
+// previous step has already copied this step's slot into the metadata buffer (prefetch_step_inputs) and the read
+// stays in device memory.  Otherwise: the mailbox slot of the device-side step counter.
+__device__ __forceinline__ void read_step_inputs(const Drmb *d, const Drmb *gate, const Mailbox *mailbox, unsigned long long *out)
 {
-    __shared__ unsigned long long s_in[2];
-    if (gate_closed(a.gate)) return;
-    const uint32_t gtid = blockIdx.x * kBlock + threadIdx.x;
-    const uint32_t gsize = gridDim.x * kBlock;
-    if (threadIdx.x == 0) { // one read of the host-resident slot per workgroup
-        const uint32_t slot = (a.gate ? a.gate->epoch - 1u : a.drmb->epoch) % kMailboxSlots;
-        s_in[0] = __hip_atomic_load(&a.mailbox->slot[slot].seeds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        s_in[1] = __hip_atomic_load(&a.mailbox->slot[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (!gate && d->pre_valid && d->pre_epoch == d->epoch) {
+        out[0] = d->pre_seeds;
+        out[1] = d->pre_key;
+        return;
     }
+    const uint32_t slot = (gate ? gate->epoch - 1u : d->epoch) % kMailboxSlots;
+    out[0] = __hip_atomic_load(&mailbox->slot[slot].seeds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    out[1] = __hip_atomic_load(&mailbox->slot[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Step entry ("ingest"): seeds -> D_0 (caller's order), their local ids and "seen" bits; step key and batch size ->
+// metadata buffer.  Out-of-range seeds are replaced by -1 (a vertex with no neighbors); a seed whose "seen" bit
+// is already set is a duplicate.  Shares its launch with the sampling of hop 0, which reads the seeds itself.
+__device__ __forceinline__ void ingest_block(const IngestArgs &a, uint32_t block, unsigned long long *s_in)
+{
+    const uint32_t gtid = block * blockDim.x + threadIdx.x;
+    if (threadIdx.x == 0) read_step_inputs(a.drmb, a.gate, a.mailbox, s_in); // one read of the host-resident slot per workgroup
     __syncthreads();
     const int32_t *seeds = reinterpret_cast<const int32_t *>(s_in[0]);
     if (gtid == 0) {
@@ -198,9 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
         d->n_exact[0] = a.batch;
         d->key_lo = (uint32_t)(s_in[1] & 0xFFFFFFFFull);
         d->key_hi = (uint32_t)(s_in[1] >> 32);
-        for (int i = 0; i < 2 * ZG_MAX_HOPS; ++i) d->ticket[i] = 0;
     }
-    for (uint64_t w = gtid; w < a.status_words; w += gsize) a.status[w] = 0;
     if (gtid < a.batch) {
         int32_t v = seeds[gtid];
         if ((uint32_t)v >= a.num_nodes) {
@@ -222,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void k_ingest(IngestArgs a)
 
 struct RelabelArgs {
     const Drmb *drmb;
-    const Drmb *gate; // consulted by the gather launch (the sampling launch has its own)
+    const Drmb *gate; // consulted by the gather launch (the hop kernel has its own)
     const int32_t *nbr;
     const int32_t *local_id;
     int32_t *col;
@@ -232,7 +263,7 @@ struct RelabelArgs {
 };
 
 // Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
-// Every sampled id is in S_h, so its map entry was written during this step (by the ingest or a compaction).
+// Every sampled id is in S_h, so its map entry was written during this step (by the ingest or a ranking tile).
 // Works for any workgroup size; a workgroup covers kRelabelPerBlock edges.
 __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t block)
 {
@@ -247,303 +278,433 @@ __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t blo
     }
 }
 
-struct SampleArgs {
+// Launch l = 0..H of the hop kernel: it samples hop l for the rows of D_l (l < H) and, for l > 0, first ranks the
+// vertices that hop l-1 discovered (they are the rows of D_l that D_{l-1} did not have).
+struct HopArgs {
     const void *offsets;
     const int32_t *indices;
     Drmb *drmb;
     const Drmb *gate;
-    const int32_t *S;
-    int32_t *row_ptr;
+    const Mailbox *mailbox;   // launch 0 reads the step's inputs itself (the gate owner's mailbox when gated)
+    int32_t *S;
+    int32_t *local_id;
+    uint32_t *bitmap_prev;    // launches 1..H: the bitmap hop l-1 filled; ranked, consumed and cleared here
+    uint32_t *bitmap_next;    // launches 0..H-1: the bitmap this launch's sampling fills
+    uint32_t *seen;
+    int32_t *row_ptr;         // block of hop l (launches 0..H-1)
     int32_t *nbr;
-    uint32_t *bitmap;
-    const uint32_t *seen;
-    uint64_t *status;
+    uint64_t *status_cnt;     // chained scan over the launch's tickets: vertices ranked ...
+    uint64_t *status_edge;    // ... and edges sampled
     uint32_t num_nodes;
-    int32_t hop;
+    int32_t launch;           // l
+    int32_t num_hops;         // H
     int32_t fanout;
-    int32_t group_log2; // lanes per frontier vertex: 2^group_log2 >= max(4, fanout)
+    int32_t group_log2;       // lanes per row: 2^group_log2 >= max(4, fanout)
     int32_t replace;
-    uint32_t tiles_per_ticket; // consecutive tiles a sampling workgroup processes
-    uint32_t blocks;    // sampling workgroups (the launch's first ones)
+    uint32_t tiles_per_ticket; // consecutive tiles of old rows per ticket
+    uint32_t cap_rows;        // capacity of n_l
+    uint32_t edge_cap;        // capacity of E_l
+    uint32_t words_per_tile;  // ranking tile (a power of two, 32..8192)
+    uint32_t rank_tiles;      // 0 for launch 0
+    uint32_t batch;
+    uint32_t blocks;          // workgroups of this role (the launch's first ones)
 };
 
-// Hop h: "row lengths", "offsets scan" and "sample" in one pass, sharing its launch with the edge relabel
-// of hop h-1 (workgroups >= sa.blocks).  A sampling workgroup has 1024 lanes; a tile is T = 1024 / G frontier
-// vertices, G = 2^group_log2 lanes per vertex, one lane per sampled slot, so that no lane ever loops over
-// slots: the step is latency-bound at mini-batch sizes and the dependent chain (ticket, frontier id, two
-// offsets, chained scan, neighbor id, "seen" word) is what sets its time.  A workgroup takes one ticket for
-// 1..4 consecutive tiles (more for large frontiers, to keep the ticket counter cool).  The first T lanes
-// compute k_i = min(F, deg) for all its tiles, their sum is chained to the predecessor tickets, then tile by
-// tile: local scan, row_ptr, and lane
-// (t, j) finds slot j's neighbor position of vertex t: j itself if deg <= F, else Floyd's subset algorithm
-// with one Philox draw per slot.  Floyd's "already chosen" test is sequential over the slots as written;
-// here it is resolved for all slots at once: the set before slot i always contains every earlier candidate,
-// plus deg-F+a for each earlier slot a that collided, so slot i collides iff an earlier slot has the same
-// candidate, or its candidate is deg-F+a for an earlier slot a that collided - an all-pairs compare with
-// independent shuffles and a short fixed-point loop.  The lane then loads the neighbor id and stores it to
-// nbr_gid (consecutive lanes, consecutive addresses).  Dedup starts here: ids already in D_h ("seen" bit,
-// an ordinary cached load) are dropped, the rest go through a hash set in LDS so that each distinct id of
-// the tile reaches the hop's bitmap with at most one device-scope atomic - popular vertices are sampled
-// hundreds of times per hop and same-address atomics serialise at the memory side.
-template <typename OffT>
-__global__ __launch_bounds__(kSampleBlock) void k_sample_hop(SampleArgs a, RelabelArgs prev)
+// LDS of a hop-kernel workgroup: up to 256 rows of the block being sampled (vertex, degree, first edge offset, row
+// length, first edge position), the dedup set of one sampling pass, scan scratch
+constexpr int kHopRows = 256;
+struct HopShared {
+    uint32_t ticket;
+    uint32_t base_cnt;
+    unsigned long long base_edge;
+    unsigned long long in[2];
+    uint32_t wsum[kHopBlock / 64];
+    uint32_t wk[4];
+    int32_t v[kHopRows];
+    uint32_t deg[kHopRows], k[kHopRows], rp[kHopRows];
+    unsigned long long off[kHopRows];
+    uint32_t set[kSampleHashSlots];
+};
+
+// One sampling pass over rows row0 .. row0 + 1024/G - 1 of the workgroup's LDS rows: lane (t, j) takes slot j of row
+// row0 + t (vertex sh.v, degree sh.deg, sh.k slots, first edge position sh.rp): j itself if deg <= F, else Floyd's
+// subset algorithm with one Philox draw per slot, all slots resolved at once (zg_floyd.h); with replacement one draw
+// per slot.  The lane loads the neighbor id and stores it to nbr_gid (consecutive lanes, consecutive addresses).
+// Dedup starts here: the ids go through a hash set in LDS so that each distinct id of the pass reaches the hop's bitmap
+// with at most one device-scope atomic - popular vertices are sampled hundreds of times per hop and same-address atomics
+// serialise at the memory side.  Ids that are already in D_l reach the bitmap too: the next launch masks it with "seen"
+// (looking every id up in "seen" here was measured: one more dependent random load per edge, slower on every workload).
+__device__ __forceinline__ void sample_pass(const HopArgs &a, HopShared &sh, uint32_t key_lo, uint32_t key_hi, uint32_t row0, int tid,
+                                            int lane)
 {
-    if (gate_closed(a.gate)) return;
-    if (blockIdx.x >= a.blocks) {
-        relabel_block(prev, blockIdx.x - a.blocks);
-        return;
-    }
-    __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[4];
-    __shared__ int32_t s_v[256];
-    __shared__ uint32_t s_deg[256], s_k[256], s_rp[256];
-    __shared__ unsigned long long s_off[256];
-    __shared__ uint32_t s_set[kSampleHashSlots];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int glog = a.group_log2;
-    const uint32_t T = (uint32_t)kSampleBlock >> glog; // vertices per tile, 16..256
-    Drmb *d = a.drmb;
-    const uint32_t n = d->n[a.hop];
-    if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop], 1u);
-    __syncthreads();
-    const uint32_t ticket = s_tile;
-    const uint32_t ntiles = (n + T - 1) / T;
-    if (n == 0 && ticket == 0 && tid == 0) {
-        a.row_ptr[0] = 0;
-        d->E[a.hop] = 0;
-    }
-    const uint32_t tile0 = ticket * a.tiles_per_ticket;
-    if (tile0 >= ntiles) return;
     const uint32_t F = (uint32_t)a.fanout;
-    const uint32_t key_lo = d->key_lo, key_hi = d->key_hi;
-
-    // ---- pass 1: row lengths of every tile of this ticket (lanes 0..255, all loads in flight together), their
-    // sum chained to the predecessor tickets.  The ticket publishes its total before any sampling starts, so
-    // later tickets never wait for more than this pass.
-    int32_t v_[kSampleMaxTpt];
-    uint32_t deg_[kSampleMaxTpt], k_[kSampleMaxTpt];
-    unsigned long long off_[kSampleMaxTpt];
-    uint32_t ksum = 0;
-    if (wave < 4) {
-        const OffT *off = (const OffT *)a.offsets;
-#pragma unroll
-        for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
-            const uint32_t i = (tile0 + sub) * T + (uint32_t)tid;
-            v_[sub] = (sub < a.tiles_per_ticket && (uint32_t)tid < T && i < n) ? a.S[i] : -1;
+    const int G = 1 << glog;
+    const int gl = lane & (G - 1);
+    const int gbase = lane & ~(G - 1);
+    const uint32_t t = row0 + ((uint32_t)tid >> glog);
+    const int32_t tv = sh.v[t];
+    const uint32_t tdeg = sh.deg[t], tk = sh.k[t], trp = sh.rp[t];
+    const unsigned long long toff = sh.off[t];
+    const bool slot = (uint32_t)gl < tk;
+    uint32_t pos = (uint32_t)gl;
+    if (a.replace) {
+        if (slot) pos = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.launch, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
+    } else {
+        const bool floyd = slot && tdeg > F;
+        if (__any(floyd)) {
+            uint32_t cand = (uint32_t)gl;
+            if (floyd)
+                cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.launch, (uint32_t)tv, (uint32_t)gl),
+                                            (uint64_t)(tdeg - F + (uint32_t)gl) + 1ull);
+            WaveGroup grp{gbase};
+            pos = floyd_position(grp, (uint32_t)gl, F, tdeg, floyd, cand);
         }
-#pragma unroll
-        for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
-            deg_[sub] = 0;
-            off_[sub] = 0;
-            if (v_[sub] >= 0) {
-                const OffT o0 = off[v_[sub]], o1 = off[v_[sub] + 1];
-                off_[sub] = (unsigned long long)o0;
-                deg_[sub] = (uint32_t)(o1 - o0);
-            }
-            k_[sub] = a.replace ? (deg_[sub] > 0 ? F : 0u) : (deg_[sub] < F ? deg_[sub] : F);
-            ksum += k_[sub];
-        }
-        const uint32_t wsum = wave_sum(ksum);
-        if (lane == 0) s_wsum[wave] = wsum;
     }
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t ticket_total = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
-        const uint32_t e = chained_exclusive_prefix(a.status, ticket, ticket_total, d, lane);
-        if (lane == 0) s_base = e;
-    }
-    __syncthreads();
-    uint32_t base = s_base;
-
-    // ---- pass 2: tile by tile
-#pragma unroll
-    for (uint32_t sub = 0; sub < kSampleMaxTpt; ++sub) {
-        const uint32_t tile = tile0 + sub;
-        if (sub >= a.tiles_per_ticket || tile >= ntiles) break; // uniform over the workgroup
-        for (int q = tid; q < kSampleHashSlots; q += kSampleBlock) s_set[q] = 0xFFFFFFFFu;
-        const uint32_t i = tile * T + (uint32_t)tid;
-        uint32_t incl = 0;
-        if (wave < 4) {
-            incl = wave_incl_scan(k_[sub], lane);
-            if (lane == 63) s_wsum[wave] = incl;
-            s_v[tid] = v_[sub];
-            s_deg[tid] = deg_[sub];
-            s_k[tid] = k_[sub];
-            s_off[tid] = off_[sub];
-        }
-        __syncthreads();
-        uint32_t wbase = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave) wbase += s_wsum[w];
-            total += s_wsum[w];
-        }
-        if (wave < 4) {
-            const uint32_t rp = base + wbase + incl - k_[sub];
-            s_rp[tid] = rp;
-            if ((uint32_t)tid < T && i < n) a.row_ptr[i] = (int32_t)rp;
-        }
-        if (tile == ntiles - 1 && tid == 0) {
-            a.row_ptr[n] = (int32_t)(base + total);
-            d->E[a.hop] = base + total;
-        }
-        base += total;
-        __syncthreads();
-
-        // ---- lane (t, gl): slot gl of the tile's vertex t
-        const int G = 1 << glog;
-        const int gl = lane & (G - 1);
-        const int gbase = lane & ~(G - 1);
-        const int t = tid >> glog;
-        const int32_t tv = s_v[t];
-        const uint32_t tdeg = s_deg[t], tk = s_k[t], trp = s_rp[t];
-        const unsigned long long toff = s_off[t];
-        const bool slot = (uint32_t)gl < tk;
-        uint32_t pos = (uint32_t)gl;
-        if (a.replace) {
-            if (slot) pos = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl), (uint64_t)tdeg);
-        } else {
-            const bool floyd = slot && tdeg > F;
-            if (__any(floyd)) {
-                uint32_t cand = (uint32_t)gl;
-                if (floyd)
-                    cand = (uint32_t)__umul64hi(philox_draw(key_lo, key_hi, (uint32_t)a.hop, (uint32_t)tv, (uint32_t)gl),
-                                                (uint64_t)(tdeg - F + (uint32_t)gl) + 1ull);
-                WaveGroup grp{gbase};
-                pos = floyd_position(grp, (uint32_t)gl, F, tdeg, floyd, cand);
-            }
-        }
-        if (slot) {
-            const int32_t g = a.indices[toff + pos];
-            a.nbr[trp + (uint32_t)gl] = g;
-            const uint32_t b = 1u << (g & 31);
-            if ((uint32_t)g < a.num_nodes && !(a.seen[(uint32_t)g >> 5] & b)) {
-                // first lane of the tile to insert g into the LDS set marks it (at most 1024 insertions into 2048 slots)
-                uint32_t h = ((uint32_t)g * 2654435761u) >> (32 - kSampleHashBits);
-                bool first = false;
-                for (;;) {
-                    const uint32_t old = atomicCAS(&s_set[h], 0xFFFFFFFFu, (uint32_t)g);
-                    if (old == 0xFFFFFFFFu) {
-                        first = true;
-                        break;
-                    }
-                    if (old == (uint32_t)g) break;
-                    h = (h + 1) & (kSampleHashSlots - 1);
+    if (slot && trp + (uint32_t)gl < a.edge_cap) {
+        const int32_t g = a.indices[toff + pos];
+        a.nbr[trp + (uint32_t)gl] = g;
+        if ((uint32_t)g < a.num_nodes) {
+            // first lane of the pass to insert g into the LDS set marks it (at most 1024 insertions into 2048 slots)
+            uint32_t h = ((uint32_t)g * 2654435761u) >> (32 - kSampleHashBits);
+            bool first = false;
+            for (;;) {
+                const uint32_t old = atomicCAS(&sh.set[h], 0xFFFFFFFFu, (uint32_t)g);
+                if (old == 0xFFFFFFFFu) {
+                    first = true;
+                    break;
                 }
-                if (first) atomicOr(&a.bitmap[(uint32_t)g >> 5], b);
+                if (old == (uint32_t)g) break;
+                h = (h + 1) & (kSampleHashSlots - 1);
             }
+            if (first) atomicOr(&a.bitmap_next[(uint32_t)g >> 5], 1u << (g & 31));
         }
-        __syncthreads(); // LDS is reused by the next tile of this ticket
     }
 }
 
-// Hop h, "compact / rank": the hop's bitmap holds exactly the new vertices (ids already in D_h never reach
-// it).  One chained pass over its |V|/32 words: the rank of a set bit is n_h + (set bits before it), so the
-// new vertices land behind D_h in ascending global id and get their local id at once.  Consumed words are
-// cleared for the next hop and their bits join "seen".  Entries beyond the cap are dropped (never written,
-// local id -1, not "seen") and the hop's overflow bit is raised.
-// A tile is 1024 * `rounds` words; each lane owns 4 * rounds consecutive words.  First the lanes count their set
-// bits, the counts are scanned inside the workgroup and the tile's total is chained to the predecessor tiles;
-// then every lane walks its words again (they come back from the cache) and expands its set bits.  Nothing is
-// kept in registers between the two walks, so the planner can trade tiles for tickets on the shared counter.
-struct CompactArgs {
-    Drmb *drmb;
-    const Drmb *gate;
-    uint32_t *bitmap;
-    uint32_t *seen;
-    int32_t *S;
-    int32_t *local_id;
-    uint64_t *status;
-    uint32_t cap_next;
-    uint32_t rounds;
-    int32_t hop;
-    int32_t last_hop; // nothing is sampled from the vertices this hop adds: their "seen" bits are not needed
-};
-
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void k_compact_hop(CompactArgs a)
+// "Row lengths" of the workgroup's LDS rows: lanes 0..255 take the vertex sh.v[tid] (-1 beyond `nrows`), load its two
+// offsets, and leave degree, first edge offset and k = min(F, deg) (F whenever deg > 0 with replacement) in LDS.
+// Returns this lane's k.
+template <typename OffT>
+__device__ __forceinline__ uint32_t load_rows(const HopArgs &a, HopShared &sh, uint32_t nrows, int tid)
 {
-    constexpr int kWaves = BLOCK / 64;
-    __shared__ uint32_t s_tile, s_base;
-    __shared__ uint32_t s_wsum[kWaves];
+    if (tid >= kHopRows) return 0u;
+    const int32_t v = (uint32_t)tid < nrows ? sh.v[tid] : -1;
+    uint32_t deg = 0;
+    unsigned long long off0 = 0;
+    if (v >= 0) {
+        const OffT *off = (const OffT *)a.offsets;
+        const OffT o0 = off[v], o1 = off[v + 1];
+        off0 = (unsigned long long)o0;
+        deg = (uint32_t)(o1 - o0);
+    }
+    const uint32_t F = (uint32_t)a.fanout;
+    const uint32_t k = a.replace ? (deg > 0 ? F : 0u) : (deg < F ? deg : F);
+    sh.v[tid] = v;
+    sh.deg[tid] = deg;
+    sh.off[tid] = off0;
+    sh.k[tid] = k;
+    return k;
+}
+
+// the lowest q set bits of x
+__device__ __forceinline__ uint32_t lowest_set_bits(uint32_t x, uint32_t q)
+{
+    uint32_t out = 0;
+    while (x && q) {
+        const uint32_t low = x & (0u - x);
+        out |= low;
+        x ^= low;
+        --q;
+    }
+    return out;
+}
+
+// The hop kernel.  A workgroup of 1024 lanes takes a ticket; tickets are handed out in start order, so every ticket a
+// workgroup ever waits for belongs to a workgroup that already runs.  In ticket order the launch's work is the row
+// order of block l:
+//   tickets 0 .. t_old-1   rows that were already in D_{l-1} (launch 0: the seeds), up to 256 per ticket;
+//   then the ranking tiles of hop l-1's bitmap, W words each, in ascending vertex id: the bits that are not "seen"
+//                          are the hop's new vertices; their rank - n_{l-1} plus the new vertices before them - is
+//                          their local id and their row in block l, so they land behind D_{l-1} in ascending id.
+// Two single-pass chained scans run over the tickets (status word = state + value, bounded wait): new vertices and
+// sampled edges.  A ticket first finds its rows' lengths k_i = min(F, deg) ("row lengths"; 256 rows at a time, held in
+// LDS), publishes both totals, takes its exclusive prefixes (wavefront 0 and wavefront 1, side by side), and then
+// writes S, the id map and row_ptr ("offsets scan") and samples its rows in passes of 1024 / G rows, one lane per
+// (row, slot) ("sample").  A ranking tile holds its bitmap words in registers (up to 8 per lane), adds the kept
+// bits to "seen" and clears the words.  Vertices ranked beyond the cap are dropped (no row, local id -1, not "seen")
+// and the hop's overflow bit is raised; the rows kept are a prefix of the row order, so the block stays consistent up
+// to the cap.  Launch H ranks only.  The launch's surplus workgroups (the grid is sized by the caps) find no ticket
+// and return.
+template <typename OffT>
+__global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel, IngestArgs ing)
+{
+    __shared__ HopShared sh;
     if (gate_closed(a.gate)) return;
+    if (blockIdx.x >= a.blocks) {
+        const uint32_t b = blockIdx.x - a.blocks;
+        if (b < rel.blocks)
+            relabel_block(rel, b);
+        else
+            ingest_block(ing, b - rel.blocks, sh.in);
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
-    if (tid == 0) s_tile = atomicAdd(&d->ticket[2 * a.hop + 1], 1u);
+    const bool first = a.launch == 0, sampling = a.launch < a.num_hops;
+    if (tid == 0) sh.ticket = atomicAdd(&d->ticket[a.launch], 1u);
+    if (first && tid == 64) read_step_inputs(d, a.gate, a.mailbox, sh.in);
+    const uint32_t n_old = first ? a.batch : d->n[a.launch - 1]; // (in flight while the ticket comes back)
+    const uint32_t key_lo_d = d->key_lo, key_hi_d = d->key_hi;
     __syncthreads();
-    const uint32_t tile = s_tile;
-    // lane `tid` owns `rounds` consecutive uint4 (4 * rounds words) of the tile, so ranks inside the tile follow
-    // (lane, word) order and one workgroup scan of the lanes' counts is enough however large the tile is
-    const size_t q0 = ((size_t)tile * BLOCK + tid) * a.rounds;
-    const uint4 *bm = reinterpret_cast<const uint4 *>(a.bitmap);
+    const uint32_t ticket = sh.ticket;
+    const uint32_t T = (uint32_t)kHopBlock >> a.group_log2;  // rows per sampling pass, 16..256
+    const uint32_t R = T * a.tiles_per_ticket;               // old rows per ticket, <= 256
+    const uint32_t t_old = sampling ? (n_old + R - 1) / R : 0u;
+    const uint32_t n_tickets = t_old + a.rank_tiles;
+    if (ticket >= n_tickets) return;
+    const bool old = ticket < t_old; // uniform over the workgroup
+    const uint32_t key_lo = first ? (uint32_t)(sh.in[1] & 0xFFFFFFFFull) : key_lo_d;
+    const uint32_t key_hi = first ? (uint32_t)(sh.in[1] >> 32) : key_hi_d;
 
-    // ---- walk 1: this lane's count
-    uint32_t cnt = 0;
-#pragma unroll 8
-    for (uint32_t r = 0; r < a.rounds; ++r) {
-        const uint4 m = bm[q0 + r];
-        cnt += __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
-    }
-    const uint32_t incl = wave_incl_scan(cnt, lane);
-    if (lane == 63) s_wsum[wave] = incl;
-    __syncthreads();
-    uint32_t wbase = 0, total = 0;
+    // ---- what this ticket's rows are
+    uint32_t m;                       // rows of this ticket: old rows, or the tile's new vertices
+    uint32_t lex = 0;                 // ranking tile: in-tile index of this lane's first new vertex
+    uint32_t nw[kHopMaxWordsPerLane]; // ranking tile: this lane's new vertices (bitmap bits that are not "seen")
+    uint32_t had = 0;                 // ... and which of its bitmap words were not empty
+    const uint32_t r0 = ticket * R;   // old rows: the first row
+    const uint32_t W = a.words_per_tile;
+    const uint32_t wpl = W >= (uint32_t)kHopBlock ? W / (uint32_t)kHopBlock : 1u;
+    const size_t w0 = old ? 0 : (size_t)(ticket - t_old) * W + (size_t)tid * wpl; // ranking tile: this lane's first word
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        if (w < wave) wbase += s_wsum[w];
-        total += s_wsum[w];
+    for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) nw[r] = 0u;
+    if (old) {
+        m = n_old - r0 < R ? n_old - r0 : R;
+    } else {
+        const bool owner = W >= (uint32_t)kHopBlock || (uint32_t)tid < W;
+        // the lane's words of the hop's bitmap, then - only where a word is not empty - the same words of "seen"
+        // (wide loads: a lane's words are consecutive)
+        auto load_words = [&](const uint32_t *src, uint32_t (&x)[kHopMaxWordsPerLane]) {
+            if (wpl == 8) {
+                const uint4 p = *reinterpret_cast<const uint4 *>(src + w0), q = *reinterpret_cast<const uint4 *>(src + w0 + 4);
+                x[0] = p.x, x[1] = p.y, x[2] = p.z, x[3] = p.w, x[4] = q.x, x[5] = q.y, x[6] = q.z, x[7] = q.w;
+            } else if (wpl == 4) {
+                const uint4 p = *reinterpret_cast<const uint4 *>(src + w0);
+                x[0] = p.x, x[1] = p.y, x[2] = p.z, x[3] = p.w;
+            } else if (wpl == 2) {
+                const uint2 p = *reinterpret_cast<const uint2 *>(src + w0);
+                x[0] = p.x, x[1] = p.y;
+            } else {
+                x[0] = src[w0];
+            }
+        };
+        if (owner) load_words(a.bitmap_prev, nw);
+#pragma unroll
+        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r)
+            if (nw[r]) had |= 1u << r;
+        if (had) {
+            uint32_t sn[kHopMaxWordsPerLane];
+#pragma unroll
+            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) sn[r] = 0u;
+            load_words(a.seen, sn);
+#pragma unroll
+            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) nw[r] &= ~sn[r];
+        }
+        uint32_t cnt = 0;
+#pragma unroll
+        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) cnt += __popc(nw[r]);
+        const uint32_t incl = wave_incl_scan(cnt, lane);
+        if (lane == 63) sh.wsum[wave] = incl;
+        __syncthreads();
+        lex = incl - cnt;
+        m = 0;
+#pragma unroll
+        for (int w = 0; w < kHopBlock / 64; ++w) {
+            if (w < wave) lex += sh.wsum[w];
+            m += sh.wsum[w];
+        }
+        __syncthreads(); // sh.wsum is used again below
     }
-    if (wave == 0) {
-        const uint32_t e = chained_exclusive_prefix(a.status, tile, total, d, lane);
-        if (lane == 0) s_base = e;
-    }
-    __syncthreads();
-    const uint32_t n_h = d->n[a.hop];
-    const uint32_t base = n_h + s_base;
 
-    // ---- walk 2: ranks and expansion over this lane's words (they come back from the cache)
-    if (cnt) {
-        uint32_t rk = base + wbase + incl - cnt;
-        for (uint32_t r = 0; r < a.rounds; ++r) {
-            const size_t q = q0 + r;
-            const uint4 m = bm[q];
-            if ((m.x | m.y | m.z | m.w) == 0) continue;
-            const uint32_t word0 = (uint32_t)q * 4u;
-            const uint32_t nw[4] = {m.x, m.y, m.z, m.w};
-            uint32_t kept[4];
+    // rows c0 .. c0 + 255 of the ticket into sh.v: old rows from the frontier list (launch 0: the seeds, an
+    // out-of-range one becoming -1, a vertex without neighbors), new vertices expanded from the lane's bitmap words
+    auto fill_rows = [&](uint32_t c0) {
+        if (old) {
+            if (tid < kHopRows && (uint32_t)tid < m) {
+                int32_t v = first ? reinterpret_cast<const int32_t *>(sh.in[0])[r0 + tid] : a.S[r0 + tid];
+                if (first && (uint32_t)v >= a.num_nodes) v = -1;
+                sh.v[tid] = v;
+            }
+        } else {
+            const uint32_t c1 = c0 + kHopRows;
+            uint32_t j = lex;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                uint32_t bits = nw[c];
-                kept[c] = 0;
-                while (bits) {
-                    const int b = __ffs((int)bits) - 1;
-                    bits &= bits - 1;
-                    const int32_t gid = (int32_t)(((word0 + c) << 5) + b);
-                    if (rk < a.cap_next) {
-                        a.S[rk] = gid;
-                        a.local_id[gid] = (int32_t)rk;
-                        kept[c] |= 1u << b;
-                    } else {
-                        a.local_id[gid] = -1;
-                    }
-                    ++rk;
+            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) {
+                uint32_t x = nw[r];
+                const uint32_t pc = __popc(x);
+                if (j + pc <= c0 || j >= c1) { // all before this batch, or this batch is full: nothing to write
+                    j += pc;
+                    continue;
+                }
+                while (x) {
+                    const int b = __ffs((int)x) - 1;
+                    x &= x - 1u;
+                    if (j >= c0 && j < c1) sh.v[j - c0] = (int32_t)((((uint32_t)w0 + r) << 5) + (uint32_t)b);
+                    ++j;
                 }
             }
-            if (!a.last_hop) { // this lane is the only writer of these words during the kernel
-                const uint4 sn = reinterpret_cast<const uint4 *>(a.seen)[q];
-                reinterpret_cast<uint4 *>(a.seen)[q] = make_uint4(sn.x | kept[0], sn.y | kept[1], sn.z | kept[2], sn.w | kept[3]);
-            }
-            reinterpret_cast<uint4 *>(a.bitmap)[q] = make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+    };
+
+    // ---- row lengths, 256 rows at a time; their total goes into the edge chain
+    const uint32_t supers = sampling ? (m + kHopRows - 1) / kHopRows : 0u;
+    uint64_t ticket_edges = 0;
+    if (sampling) {
+        uint32_t ksum = 0;
+        for (uint32_t q = 0; q < supers; ++q) {
+            const uint32_t c0 = q * kHopRows;
+            fill_rows(c0);
+            ksum += load_rows<OffT>(a, sh, m - c0 < (uint32_t)kHopRows ? m - c0 : (uint32_t)kHopRows, tid);
+            if (q + 1 < supers) __syncthreads(); // the next fill overwrites sh.v
+        }
+        if (wave < 4) {
+            const uint32_t ws = wave_sum(ksum);
+            if (lane == 0) sh.wk[wave] = ws;
+        }
+        __syncthreads();
+        ticket_edges = (uint64_t)sh.wk[0] + sh.wk[1] + sh.wk[2] + sh.wk[3];
+    }
+    // ---- both chains, side by side: wavefront 0 looks back over the new-vertex counts, wavefront 1 over the edge
+    // counts.  Old rows hold no new vertex: their count chain entry is an inclusive prefix at once.
+    if (wave == 0) {
+        if (old) {
+            if (lane == 0) st_store(&a.status_cnt[ticket], kStPrefix);
+        } else {
+            const uint64_t r = chained_exclusive_prefix(a.status_cnt, ticket, (uint64_t)m, d, lane);
+            if (lane == 0) sh.base_cnt = (uint32_t)r;
         }
     }
-    if (tile == gridDim.x - 1 && tid == 0) {
-        const uint32_t exact = base + total;
-        d->n_exact[a.hop + 1] = exact;
-        d->n[a.hop + 1] = exact < a.cap_next ? exact : a.cap_next;
-        if (exact > a.cap_next) {
-            atomicOr(&d->flags, ZG_FLAG_HOP_OVERFLOW(a.hop));
-            atomicOr(&d->step_flags, ZG_FLAG_HOP_OVERFLOW(a.hop));
+    if (wave == 1 && sampling) {
+        const uint64_t e = chained_exclusive_prefix(a.status_edge, ticket, ticket_edges, d, lane);
+        if (lane == 0) sh.base_edge = e;
+    }
+    __syncthreads();
+    const uint32_t rank0 = old ? r0 : n_old + sh.base_cnt;                       // row index of the ticket's first row
+    const uint32_t room = rank0 < a.cap_rows ? a.cap_rows - rank0 : 0u;          // how many of its rows fit (old rows: all)
+    uint64_t ebase = sampling ? sh.base_edge : 0ull;
+
+    if (sampling) {
+        // ---- offsets scan + sample, 256 rows at a time.  A single batch of rows is still in LDS from above; several
+        // are redone (their loads hit the cache).
+        for (uint32_t q = 0; q < supers; ++q) {
+            const uint32_t c0 = q * kHopRows;
+            const uint32_t nrows = m - c0 < (uint32_t)kHopRows ? m - c0 : (uint32_t)kHopRows;
+            const uint32_t keep = room > c0 ? (room - c0 < nrows ? room - c0 : nrows) : 0u;
+            if (supers > 1) {
+                fill_rows(c0);
+                (void)load_rows<OffT>(a, sh, nrows, tid);
+            }
+            uint32_t k = 0, kincl = 0;
+            if (wave < 4) {
+                k = (uint32_t)tid < keep ? sh.k[tid] : 0u; // dropped rows sample nothing
+                kincl = wave_incl_scan(k, lane);
+                if (lane == 63) sh.wsum[wave] = kincl;
+            }
+            __syncthreads();
+            uint32_t total = 0;
+            if (wave < 4) {
+                uint32_t wbase = 0;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    if (w < wave) wbase += sh.wsum[w];
+                const uint32_t rp = (uint32_t)ebase + wbase + kincl - k;
+                sh.k[tid] = k;
+                sh.rp[tid] = rp;
+                if ((uint32_t)tid < keep) {
+                    a.row_ptr[rank0 + c0 + tid] = (int32_t)rp;
+                    if (!old) {
+                        const int32_t gid = sh.v[tid];
+                        a.S[rank0 + c0 + tid] = gid;
+                        a.local_id[gid] = (int32_t)(rank0 + c0 + tid);
+                    }
+                } else if ((uint32_t)tid < nrows) {
+                    a.local_id[sh.v[tid]] = -1;
+                }
+            }
+            total = sh.wsum[0] + sh.wsum[1] + sh.wsum[2] + sh.wsum[3];
+            ebase += total;
+            for (uint32_t row0 = 0; row0 < keep; row0 += T) {
+                for (int x = tid; x < kSampleHashSlots; x += kHopBlock) sh.set[x] = 0xFFFFFFFFu;
+                __syncthreads();
+                sample_pass(a, sh, key_lo, key_hi, row0, tid, lane);
+                __syncthreads(); // the set is reset by the next pass, the LDS rows are reused by the next batch
+            }
+        }
+    } else {
+        // ---- closing launch: ranks only
+        uint32_t j = lex;
+#pragma unroll
+        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) {
+            uint32_t x = nw[r];
+            while (x) {
+                const int b = __ffs((int)x) - 1;
+                x &= x - 1u;
+                const int32_t gid = (int32_t)((((uint32_t)w0 + r) << 5) + (uint32_t)b);
+                if (j < room) {
+                    a.S[rank0 + j] = gid;
+                    a.local_id[gid] = (int32_t)(rank0 + j);
+                } else {
+                    a.local_id[gid] = -1;
+                }
+                ++j;
+            }
+        }
+    }
+
+    if (old) {
+        if (first && ticket == t_old - 1 && tid == 0) { // launch 0 has no ranking tiles: the block ends with these rows
+            a.row_ptr[n_old] = (int32_t)ebase;
+            d->E[a.launch] = (uint32_t)ebase;
+        }
+        return;
+    }
+
+    // ---- the kept vertices join "seen" (not after the last hop: nothing is sampled from them), consumed words are
+    // cleared for the hop after next; this lane is the only writer of its words during the launch
+    if (had) {
+        uint32_t left = lex < room ? room - lex : 0u; // how many of this lane's vertices are kept
+#pragma unroll
+        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r)
+            if (had & (1u << r)) {
+                const uint32_t pc = __popc(nw[r]);
+                if (sampling && nw[r]) {
+                    const uint32_t keep = left >= pc ? nw[r] : lowest_set_bits(nw[r], left);
+                    if (keep) __hip_atomic_fetch_or(&a.seen[w0 + r], keep, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // no value comes back: nothing to wait for
+                }
+                left = left >= pc ? left - pc : 0u;
+                a.bitmap_prev[w0 + r] = 0u;
+            }
+    }
+
+    // ---- end of the block: the tile in which the cap falls closes a truncated block; the last ticket publishes the
+    // hop's sizes and, when everything fitted, closes the block
+    if (tid == 0) {
+        if (sampling && rank0 <= a.cap_rows && (uint64_t)rank0 + m > a.cap_rows) {
+            a.row_ptr[a.cap_rows] = (int32_t)ebase;
+            d->E[a.launch] = (uint32_t)ebase;
+        }
+        if (ticket == n_tickets - 1) {
+            const uint64_t exact = (uint64_t)rank0 + m;
+            d->n_exact[a.launch] = (uint32_t)exact;
+            d->n[a.launch] = exact < a.cap_rows ? (uint32_t)exact : a.cap_rows;
+            if (exact > a.cap_rows) {
+                atomicOr(&d->flags, ZG_FLAG_HOP_OVERFLOW(a.launch - 1));
+                atomicOr(&d->step_flags, ZG_FLAG_HOP_OVERFLOW(a.launch - 1));
+            } else if (sampling) {
+                a.row_ptr[exact] = (int32_t)ebase;
+                d->E[a.launch] = (uint32_t)ebase;
+            }
         }
     }
 }
@@ -557,17 +718,37 @@ struct FinishArgs {
     const int32_t *S;
     uint32_t *seen;
     uint32_t *log;
+    uint64_t *status;       // the chained scans' status words of every launch: back to zero for the next step
+    uint64_t status_words;
     int32_t num_hops;
     uint32_t blocks; // workgroups given to this role (0: role absent)
 };
 
 // End of step: the "seen" words of this step's frontier vertices (everything in D_{H-1}: the seeds and
-// what hops 0..H-2 added) go back to zero - the bitmaps over |V| are never cleared as a whole - and the
-// step is appended to the device-side log; the step counter advances.
+// what hops 0..H-2 added) go back to zero - the bitmaps over |V| are never cleared as a whole -, the scan
+// state (status words, tile tickets) restarts for the next step, and the step is appended to the device-side
+// log; the step counter advances.
 // last launch of a step that carries a gated twin: the owner's step is complete whether or not the twin ran
 __device__ __forceinline__ void publish_gate_owner(const FinishArgs &a)
 {
     __hip_atomic_store(&a.gate_mailbox->completed, a.gate->epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// One lane, early in the step's last launch: if the host has already handed over the next step, its mailbox slot is
+// copied into the metadata buffer, so that the next step starts without a read of host memory.
+__device__ __forceinline__ void prefetch_step_inputs(Drmb *d, const Mailbox *mailbox)
+{
+    const uint32_t next = d->epoch + 1u;
+    const uint32_t issued = __hip_atomic_load(&mailbox->issued, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if ((int32_t)(issued - (next + 1u)) >= 0) {
+        const uint32_t slot = next % kMailboxSlots;
+        d->pre_seeds = __hip_atomic_load(&mailbox->slot[slot].seeds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        d->pre_key = __hip_atomic_load(&mailbox->slot[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        d->pre_epoch = next;
+        d->pre_valid = 1u;
+    } else {
+        d->pre_valid = 0u;
+    }
 }
 
 __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block)
@@ -578,8 +759,10 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         const int32_t g = a.S[i];
         if (g >= 0) a.seen[(uint32_t)g >> 5] = 0u;
     }
+    for (uint64_t w = i; w < a.status_words; w += (uint64_t)a.blocks * kBlock) a.status[w] = 0ull;
     if (i == 0) {
         Drmb *d = a.drmb;
+        for (int l = 0; l <= a.num_hops; ++l) d->ticket[l] = 0u;
         const uint32_t epoch = d->epoch;
         uint32_t *rec = a.log + (size_t)(epoch % kLogCapacity) * ZG_LOG_STRIDE;
         int p = 0;
@@ -747,6 +930,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(RowArgs agg, FinishArgs fi
         if (blockIdx.x == 0 && threadIdx.x == 0) publish_gate_owner(fin);
         return;
     }
+    // the launch's first workgroup starts early in the launch: its first lane looks whether the next step is already there
+    if (blockIdx.x == 0 && threadIdx.x == 0 && fin.blocks && !fin.gate) prefetch_step_inputs(fin.drmb, fin.mailbox);
     if (blockIdx.x < agg.blocks)
         aggregate_block<VEC>(agg, blockIdx.x, s_mem);
     else
@@ -936,11 +1121,11 @@ struct zg_plan_s {
     float *X() const { return lay.feat_dim > 0 ? reinterpret_cast<float *>(ws + lay.off_X) : nullptr; }
     float *agg() const { return lay.feat_dim > 0 ? reinterpret_cast<float *>(ws + lay.off_agg) : nullptr; }
     int32_t *local_id() const { return reinterpret_cast<int32_t *>(ws + lay.off_local_id); }
-    uint32_t *bitmap() const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap); }
+    uint32_t *bitmap(int hop) const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap[hop & 1]); } // the one hop `hop` fills
     uint32_t *seen() const { return reinterpret_cast<uint32_t *>(ws + lay.off_seen); }
     uint64_t *status() const { return reinterpret_cast<uint64_t *>(ws + lay.off_status); }
-    uint64_t *status_sample(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_sample[h]); }
-    uint64_t *status_compact(int h) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_compact[h]); }
+    uint64_t *status_cnt(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_cnt[l]); }
+    uint64_t *status_edge(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_edge[l]); }
 };
 
 namespace {
@@ -977,6 +1162,8 @@ FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate =
     fa.S = p->S();
     fa.seen = p->seen();
     fa.log = p->log();
+    fa.status = p->status();
+    fa.status_words = p->lay.status_words;
     fa.num_hops = H;
     fa.blocks = (uint32_t)((p->lay.node_cap[H - 1] + kBlock - 1) / kBlock);
     return fa;
@@ -1053,80 +1240,64 @@ int launch_aggregate(int vec, const RowArgs &agg, const FinishArgs &fa, hipStrea
     return ZG_OK;
 }
 
-int launch_ingest(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate)
-{
-    IngestArgs a;
-    a.drmb = p->drmb();
-    a.gate = gate ? gate->drmb() : nullptr;
-    a.mailbox = gate ? gate->mailbox_dev : p->mailbox_dev;
-    a.S = p->S();
-    a.local_id = p->local_id();
-    a.seen = p->seen();
-    a.status = p->status();
-    a.status_words = p->lay.status_words;
-    a.batch = (uint32_t)p->batch;
-    a.num_nodes = (uint32_t)p->graph->num_nodes;
-    const uint64_t work = std::max<uint64_t>((uint64_t)p->batch, std::min<uint64_t>(a.status_words, 1u << 16));
-    const unsigned grid = (unsigned)((work + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(k_ingest, dim3(grid), dim3(kBlock), 0, st, a);
-    ZG_HIP(hipGetLastError());
-    return ZG_OK;
-}
-
-// a whole step, in order, on one stream (captured once, or issued eagerly).  With `gate` the kernels are those
-// of gate's worst-case twin `p`, run on gate's inputs and only if gate's step overflowed; `defer_completed`
-// marks a plan whose gated twin follows in the same sequence.
+// a whole step, in order, on one stream (captured once, or issued eagerly): the hop kernel's launches 0..H, then the
+// two feature launches.  With `gate` the kernels are those of gate's worst-case twin `p`, run on gate's inputs and
+// only if gate's step overflowed; `defer_completed` marks a plan whose gated twin follows in the same sequence.
 int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nullptr, bool defer_completed = false)
 {
     const Layout &L = p->lay;
     const zg_graph_t *g = p->graph;
     const int H = L.num_hops;
-    int rc0 = launch_ingest(p, st, gate);
-    if (rc0 != ZG_OK) return rc0;
-    for (int h = 0; h < H; ++h) {
-        SampleArgs sa;
-        std::memset(&sa, 0, sizeof(sa));
-        sa.offsets = g->d_offsets;
-        sa.indices = g->d_indices;
-        sa.drmb = p->drmb();
-        sa.gate = gate ? gate->drmb() : nullptr;
-        sa.S = p->S();
-        sa.row_ptr = p->row_ptr(h);
-        sa.nbr = p->nbr(h);
-        sa.bitmap = p->bitmap();
-        sa.seen = p->seen();
-        sa.status = p->status_sample(h);
-        sa.num_nodes = (uint32_t)g->num_nodes;
-        sa.hop = h;
-        sa.fanout = L.fanout[h];
-        sa.group_log2 = sample_group_log2(L.fanout[h]);
-        sa.replace = (p->flags & ZG_PLAN_REPLACE) ? 1 : 0;
-        sa.tiles_per_ticket = (uint32_t)L.sample_tpt[h];
-        sa.blocks = (uint32_t)L.sample_blocks[h];
-        const RelabelArgs ra = relabel_args(p, h - 1, h > 0);
-        const unsigned gs = sa.blocks + ra.blocks;
+    for (int l = 0; l <= H; ++l) {
+        HopArgs ha;
+        std::memset(&ha, 0, sizeof(ha));
+        ha.offsets = g->d_offsets;
+        ha.indices = g->d_indices;
+        ha.drmb = p->drmb();
+        ha.gate = gate ? gate->drmb() : nullptr;
+        ha.mailbox = gate ? gate->mailbox_dev : p->mailbox_dev;
+        ha.S = p->S();
+        ha.local_id = p->local_id();
+        ha.bitmap_prev = l > 0 ? p->bitmap(l - 1) : nullptr;
+        ha.bitmap_next = l < H ? p->bitmap(l) : nullptr;
+        ha.seen = p->seen();
+        ha.row_ptr = l < H ? p->row_ptr(l) : nullptr;
+        ha.nbr = l < H ? p->nbr(l) : nullptr;
+        ha.status_cnt = p->status_cnt(l);
+        ha.status_edge = p->status_edge(l);
+        ha.num_nodes = (uint32_t)g->num_nodes;
+        ha.launch = l;
+        ha.num_hops = H;
+        ha.fanout = l < H ? L.fanout[l] : 1;
+        ha.group_log2 = sample_group_log2(ha.fanout);
+        ha.replace = (p->flags & ZG_PLAN_REPLACE) ? 1 : 0;
+        ha.tiles_per_ticket = l < H ? (uint32_t)L.old_tpt[l] : 1u;
+        ha.cap_rows = (uint32_t)L.node_cap[l];
+        ha.edge_cap = l < H ? (uint32_t)L.edge_cap[l] : 0u;
+        ha.words_per_tile = l > 0 ? (uint32_t)L.tile_words[l] : (uint32_t)kHopMinTileWords;
+        ha.rank_tiles = (uint32_t)L.rank_tiles[l];
+        ha.batch = (uint32_t)p->batch;
+        ha.blocks = (uint32_t)(L.old_tickets[l] + L.rank_tiles[l]);
+        // the edges of hop l-2 can be relabeled now: launch l-1 ranked the last vertices they point to
+        const RelabelArgs ra = relabel_args(p, l - 2, l >= 2);
+        IngestArgs ia;
+        std::memset(&ia, 0, sizeof(ia));
+        if (l == 0) {
+            ia.drmb = p->drmb();
+            ia.gate = ha.gate;
+            ia.mailbox = ha.mailbox;
+            ia.S = p->S();
+            ia.local_id = p->local_id();
+            ia.seen = p->seen();
+            ia.batch = (uint32_t)p->batch;
+            ia.num_nodes = (uint32_t)g->num_nodes;
+            ia.blocks = (uint32_t)((p->batch + kHopBlock - 1) / kHopBlock);
+        }
+        const unsigned grid = ha.blocks + ra.blocks + ia.blocks;
         if (g->offsets_dtype == ZG_I64)
-            hipLaunchKernelGGL(k_sample_hop<int64_t>, dim3(gs), dim3(kSampleBlock), 0, st, sa, ra);
+            hipLaunchKernelGGL(k_hop<int64_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia);
         else
-            hipLaunchKernelGGL(k_sample_hop<int32_t>, dim3(gs), dim3(kSampleBlock), 0, st, sa, ra);
-        ZG_HIP(hipGetLastError());
-
-        CompactArgs ca;
-        ca.drmb = p->drmb();
-        ca.gate = gate ? gate->drmb() : nullptr;
-        ca.bitmap = p->bitmap();
-        ca.seen = p->seen();
-        ca.S = p->S();
-        ca.local_id = p->local_id();
-        ca.status = p->status_compact(h);
-        ca.cap_next = (uint32_t)L.node_cap[h + 1];
-        ca.hop = h;
-        ca.last_hop = h == H - 1 ? 1 : 0;
-        ca.rounds = (uint32_t)L.compact_sub;
-        if (L.compact_block == kCompactBlockLarge)
-            hipLaunchKernelGGL(k_compact_hop<kCompactBlockLarge>, dim3((unsigned)L.compact_tiles), dim3(kCompactBlockLarge), 0, st, ca);
-        else
-            hipLaunchKernelGGL(k_compact_hop<kCompactBlockSmall>, dim3((unsigned)L.compact_tiles), dim3(kCompactBlockSmall), 0, st, ca);
+            hipLaunchKernelGGL(k_hop<int32_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia);
         ZG_HIP(hipGetLastError());
     }
     // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all
@@ -1226,7 +1397,8 @@ static int make_plan_object(zg_plan_t **out, const zg_graph_t *g, const Layout &
     if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_log, 0, (size_t)kLogCapacity * ZG_LOG_STRIDE * 4, st);
     if (init_scratch) {
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_seen, 0, (size_t)L.bitmap_words * 4, st);
-        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap, 0, (size_t)L.bitmap_words * 4, st);
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[0], 0, (size_t)L.bitmap_words * 4, st);
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[1], 0, (size_t)L.bitmap_words * 4, st);
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -1360,6 +1532,7 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     p->mailbox->slot[slot].key = rng_key;
     std::atomic_thread_fence(std::memory_order_seq_cst);
     p->issued += 1;
+    reinterpret_cast<std::atomic<uint32_t> *>(&p->mailbox->issued)->store(p->issued, std::memory_order_release); // the slot is filled
     int rc = ZG_OK;
     if (p->flags & ZG_PLAN_EAGER) {
         rc = enqueue_step(p, st);
@@ -1371,6 +1544,7 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     }
     if (rc != ZG_OK) {
         p->issued -= 1; // nothing was enqueued: the slot is free again
+        reinterpret_cast<std::atomic<uint32_t> *>(&p->mailbox->issued)->store(p->issued, std::memory_order_release);
     } else {
         p->last_stream = st;
         p->stepped = true;

@@ -47,7 +47,7 @@ int sample_group_log2(int fanout)
     return g;
 }
 
-int64_t sample_tile_nodes(int fanout) { return kSampleBlock >> sample_group_log2(fanout); }
+int64_t sample_tile_nodes(int fanout) { return kHopBlock >> sample_group_log2(fanout); }
 
 // ---- envelope ----------------------------------------------------------------------------------
 
@@ -79,12 +79,13 @@ static void relocate(Layout &L, size_t env_base, size_t scratch_base)
         env(L.off_agg);
     }
     scr(L.off_local_id);
-    scr(L.off_bitmap);
+    scr(L.off_bitmap[0]);
+    scr(L.off_bitmap[1]);
     scr(L.off_seen);
     scr(L.off_status);
-    for (int h = 0; h < L.num_hops; ++h) {
-        scr(L.off_status_sample[h]);
-        scr(L.off_status_compact[h]);
+    for (int l = 0; l <= L.num_hops; ++l) {
+        scr(L.off_status_cnt[l]);
+        scr(L.off_status_edge[l]);
     }
 }
 
@@ -213,29 +214,40 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.edge_cap[h] = L.node_cap[h] * fanouts[h];
         if (L.edge_cap[h] >= (int64_t)1 << 31) return fail(ZG_EINVAL, "edge capacity of a hop reaches 2^31");
         pi.edge_cap[h] = L.edge_cap[h];
-        L.sample_tiles[h] = (L.node_cap[h] + sample_tile_nodes(fanouts[h]) - 1) / sample_tile_nodes(fanouts[h]);
-        // every tile takes a ticket from one device-wide counter, and same-address atomics serialise
-        // (about 15 ns each on MI355X): large frontiers give a workgroup several consecutive tiles per ticket
-        L.sample_tpt[h] = 1;
-        while (L.sample_tpt[h] < kSampleMaxTpt && L.sample_tiles[h] > max_tickets * L.sample_tpt[h]) L.sample_tpt[h] *= 2;
-        L.sample_blocks[h] = (L.sample_tiles[h] + L.sample_tpt[h] - 1) / L.sample_tpt[h];
     }
     {
+        // Launch l of the hop kernel (l = 0..H) samples hop l for the rows of D_l and, for l > 0, first ranks the vertices
+        // hop l-1 discovered.  Rows that were already in D_{l-1} come in tiles of 1024 / G rows, a ticket covering 1..4
+        // tiles (every ticket is one atomic on a shared counter, about 15 ns each on MI355X, hence the budget).  The
+        // discovered vertices come in ranking tiles: W consecutive words of the hop's bitmap per workgroup, W a power of
+        // two chosen so that a tile holds about one sampling pass (1024 / G vertices) of new rows at the cap, within the
+        // ticket budget and between 32 and 8192 words.
         const int64_t words = (V + 31) / 32;
-        // compaction tiles: a workgroup of 256 lanes takes 1024 words per round; when the bitmap has more words than
-        // the ticket budget covers in one round, workgroups of 1024 lanes (4096 words per round, half the ticket
-        // budget) take over and rounds double until the tile count fits.  Measured: at 250 k vertices many small
-        // workgroups win (the expansion's scattered stores spread over more CUs: 7 vs 13 us); at 110 M vertices the
-        // large ones do (a short look-back chain: 210 tiles of 4 rounds, 262 vs 280 us per step).
-        const bool large = words > max_tickets * 4 * kCompactBlockSmall;
-        L.compact_block = large ? kCompactBlockLarge : kCompactBlockSmall;
-        const int64_t budget = large ? std::max<int64_t>(1, max_tickets / 2) : max_tickets;
-        const int64_t round_words = 4 * (int64_t)L.compact_block;
-        L.compact_sub = 1;
-        while (L.compact_sub < 4096 && words > budget * round_words * L.compact_sub) L.compact_sub *= 2;
-        const size_t tile_words = (size_t)round_words * L.compact_sub;
-        L.bitmap_words = (int64_t)align_up((size_t)words, tile_words);
-        L.compact_tiles = L.bitmap_words / (int64_t)tile_words;
+        L.bitmap_words = (int64_t)align_up((size_t)words, (size_t)kHopMaxTileWords);
+        for (int l = 0; l <= num_hops; ++l) {
+            // The launch's tickets share one budget: workgroups beyond what the chip holds at once (two of 1024 lanes per
+            // compute unit) only start when earlier ones have finished - a second round that doubles the launch's time.
+            const int64_t rows = l == 0 ? batch : L.node_cap[l - 1];
+            const int64_t T = l < num_hops ? sample_tile_nodes(fanouts[l]) : 256;
+            const int64_t fattest_old = l < num_hops ? (rows + 255) / 256 : 0; // old tickets if each took 256 rows
+            if (l > 0) {
+                const int64_t budget = std::max<int64_t>(std::max<int64_t>(1, max_tickets / 2), max_tickets - fattest_old);
+                const int64_t want = std::max<int64_t>(1, std::min<int64_t>(budget, (L.node_cap[l] + T - 1) / T));
+                int64_t W = kHopMinTileWords;
+                while (W < kHopMaxTileWords && W * want < words) W *= 2;
+                L.tile_words[l] = (int32_t)W;
+                L.rank_tiles[l] = (words + W - 1) / W;
+            }
+            if (l < num_hops) {
+                L.old_tiles[l] = (rows + T - 1) / T;
+                L.old_tpt[l] = 1;
+                // (a ticket's rows are held in 256 LDS entries)
+                while (L.old_tpt[l] < kHopMaxTpt && 2 * L.old_tpt[l] * T <= 256 &&
+                       (L.old_tiles[l] + L.old_tpt[l] - 1) / L.old_tpt[l] + L.rank_tiles[l] > max_tickets)
+                    L.old_tpt[l] *= 2;
+                L.old_tickets[l] = (L.old_tiles[l] + L.old_tpt[l] - 1) / L.old_tpt[l];
+            }
+        }
     }
 
     size_t off = 0;
@@ -267,19 +279,18 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     }
     L.envelope_end = off;
     L.off_local_id = place((size_t)V * 4);
-    L.off_bitmap = place((size_t)L.bitmap_words * 4);
+    L.off_bitmap[0] = place((size_t)L.bitmap_words * 4); // the bitmap hop h fills is [h & 1]: launch h+1 ranks and clears it
+    L.off_bitmap[1] = place((size_t)L.bitmap_words * 4); // while its own sampling fills the other one
     L.off_seen = place((size_t)L.bitmap_words * 4);
     L.status_words = 0;
-    for (int h = 0; h < num_hops; ++h) L.status_words += (size_t)L.sample_tiles[h] + (size_t)L.compact_tiles;
+    for (int l = 0; l <= num_hops; ++l) L.status_words += 2 * ((size_t)L.old_tickets[l] + (size_t)L.rank_tiles[l]);
     L.off_status = place(L.status_words * 8);
     size_t w = 0;
-    for (int h = 0; h < num_hops; ++h) {
-        L.off_status_sample[h] = L.off_status + w * 8;
-        w += (size_t)L.sample_tiles[h];
-    }
-    for (int h = 0; h < num_hops; ++h) {
-        L.off_status_compact[h] = L.off_status + w * 8;
-        w += (size_t)L.compact_tiles;
+    for (int l = 0; l <= num_hops; ++l) {
+        const size_t n = (size_t)L.old_tickets[l] + (size_t)L.rank_tiles[l];
+        L.off_status_cnt[l] = L.off_status + w * 8;
+        L.off_status_edge[l] = L.off_status + (w + n) * 8;
+        w += 2 * n;
     }
     L.total = off;
 
@@ -288,10 +299,10 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
     pi.workspace_bytes = (int64_t)L.total;
     pi.maxsg_envelope_bytes = envelope_bytes_for(pi.maxsg_nodes);
     for (int h = 0; h < num_hops; ++h) {
-        pi.grid_sample[h] = (int32_t)L.sample_blocks[h];
+        pi.grid_sample[h] = (int32_t)(L.old_tickets[h] + L.rank_tiles[h]);
         pi.grid_relabel[h] = (int32_t)((L.edge_cap[h] + kRelabelPerBlock - 1) / kRelabelPerBlock);
     }
-    pi.grid_compact = (int32_t)L.compact_tiles;
+    pi.grid_compact = (int32_t)L.rank_tiles[num_hops];
     if (feat_dim > 0) {
         RowTiling tg = gather_tiling(feat_dim, true), ta = aggregate_tiling(feat_dim, true);
         pi.grid_gather = (int32_t)((L.x_rows + tg.rows - 1) / tg.rows);
@@ -433,7 +444,10 @@ int zg_graph_create(zg_graph_t **out, int64_t num_nodes, int64_t num_edges, cons
     g->d_offsets = d_offsets;
     g->offsets_dtype = offsets_dtype;
     g->d_indices = d_indices;
-    if (hipGetDevice(&g->device) != hipSuccess) { delete g; return fail(ZG_EHIP, "hipGetDevice failed"); }
+    {
+        const hipError_t e = hipGetDevice(&g->device);
+        if (e != hipSuccess) { delete g; return fail(ZG_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e)); }
+    }
 
     // one read-back of the offsets (init time): degree statistics for the envelope model + sanity checks
     std::vector<int64_t> deg((size_t)num_nodes);

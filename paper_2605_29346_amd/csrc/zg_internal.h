@@ -12,11 +12,12 @@
 namespace zg {
 
 constexpr int kBlock = 256;             // threads per workgroup (4 wavefronts of 64)
-constexpr int kSampleBlock = 1024;      // threads per sampling workgroup: (1024 / G) frontier vertices x G slots
-constexpr int kCompactBlockSmall = 256;  // threads per compaction workgroup (each takes one uint4 = 4 bitmap words per round) ...
-constexpr int kCompactBlockLarge = 1024; // ... and for bitmaps beyond the ticket budget of the small ones
-constexpr int kMaxTickets = 512;        // tiles are sized so that a kernel's ticket counter sees about this many atomics
-constexpr int kSampleMaxTpt = 4;        // most consecutive tiles a sampling workgroup takes per ticket
+constexpr int kHopBlock = 1024;         // threads per workgroup of the hop kernel: (1024 / G) vertices x G slots when it samples
+constexpr int kMaxTickets = 480;        // tickets per launch of the hop kernel: what 256 compute units hold at once (2 x 1024 lanes each), less a margin
+constexpr int kHopMaxTpt = 4;           // most consecutive tiles of frontier rows a workgroup takes per ticket
+constexpr int kHopMaxWordsPerLane = 8;  // bitmap words a lane owns in a ranking tile (held in registers)
+constexpr int kHopMinTileWords = 32;    // smallest ranking tile: 32 words = 1024 vertices
+constexpr int kHopMaxTileWords = kHopBlock * kHopMaxWordsPerLane; // largest: 8192 words = 262144 vertices
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
 constexpr uint64_t kGatherStreamBytes = 160ull << 20; // gathered matrices above this size are copied with non-temporal accesses
@@ -37,8 +38,10 @@ struct Drmb {
     uint32_t last_flags;               // step_flags of the step that finished last (step_flags itself restarts at 0)
     uint32_t epoch;                    // steps run so far
     uint32_t key_lo, key_hi;           // step key
-    uint32_t ticket[2 * ZG_MAX_HOPS];  // tile tickets: [2h] sampling, [2h+1] compaction
+    uint32_t ticket[ZG_MAX_HOPS + 1];  // tile tickets of the hop kernel's launches 0..H
     uint32_t active;                   // ZG_PLAN_AUTO_FALLBACK: 1 when the last step's valid outputs are the twin's
+    uint32_t pre_valid, pre_epoch;     // the next step's inputs, copied from the host mailbox ahead of time: valid for step pre_epoch
+    unsigned long long pre_seeds, pre_key;
 };
 
 struct Layout {
@@ -50,21 +53,21 @@ struct Layout {
     int64_t node_cap[ZG_MAX_HOPS + 1] = {};
     int64_t edge_cap[ZG_MAX_HOPS] = {};
     int32_t fanout[ZG_MAX_HOPS] = {};
-    int64_t bitmap_words = 0; // padded to whole compaction tiles
-    int64_t sample_tiles[ZG_MAX_HOPS] = {};   // tiles of 1024 / G frontier vertices
-    int32_t sample_tpt[ZG_MAX_HOPS] = {};     // consecutive tiles one sampling workgroup takes per ticket (1..kSampleMaxTpt)
-    int64_t sample_blocks[ZG_MAX_HOPS] = {};  // sampling workgroups = ceil(tiles / tiles per ticket)
-    int32_t compact_block = 256;              // threads per compaction workgroup
-    int32_t compact_sub = 1;                  // rounds (of 4 words per thread) per compaction tile (a power of two)
-    int64_t compact_tiles = 0;
+    int64_t bitmap_words = 0; // padded to whole ranking tiles of the largest size
+    // launch l = 0..H of the hop kernel samples hop l (l < H) and ranks the vertices that hop l-1 discovered (l > 0)
+    int64_t old_tiles[ZG_MAX_HOPS] = {};        // launch l < H: tiles of 1024 / G rows of the previous frontier (cap)
+    int32_t old_tpt[ZG_MAX_HOPS] = {};          // consecutive such tiles per ticket (1..kHopMaxTpt)
+    int64_t old_tickets[ZG_MAX_HOPS + 1] = {};  // = ceil(tiles / tiles per ticket); 0 for launch H
+    int32_t tile_words[ZG_MAX_HOPS + 1] = {};   // launch l > 0: bitmap words per ranking tile (a power of two)
+    int64_t rank_tiles[ZG_MAX_HOPS + 1] = {};   // launch l > 0: ranking tiles; 0 for launch 0
     // byte offsets into the workspace
     size_t off_drmb = 0, off_log = 0, off_S = 0;
     size_t off_row_ptr[ZG_MAX_HOPS] = {}, off_nbr[ZG_MAX_HOPS] = {}, off_col[ZG_MAX_HOPS] = {};
     size_t off_X = 0, off_agg = 0;
     size_t envelope_end = 0;
-    size_t off_local_id = 0, off_bitmap = 0, off_seen = 0, off_status = 0;
-    size_t status_words = 0; // uint64 words: sampling tiles of every hop, then compaction tiles of every hop
-    size_t off_status_sample[ZG_MAX_HOPS] = {}, off_status_compact[ZG_MAX_HOPS] = {};
+    size_t off_local_id = 0, off_bitmap[2] = {}, off_seen = 0, off_status = 0;
+    size_t status_words = 0; // uint64 words: per launch, one vertex-count chain and one edge-count chain over its tickets
+    size_t off_status_cnt[ZG_MAX_HOPS + 1] = {}, off_status_edge[ZG_MAX_HOPS + 1] = {};
     size_t total = 0;
 };
 

@@ -76,6 +76,7 @@ def lib() -> C.CDLL:
     is (re)built when hipcc is there; otherwise this raises: there is no fallback path."""
     global _lib
     if _lib is None:
+        import torch  # noqa: F401  (first: the library must bind to the HIP runtime PyTorch brings, not load a second one)
         from . import build as _build
         _build.ensure_current()
         if not os.path.exists(_LIB_PATH):

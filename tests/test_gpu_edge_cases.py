@@ -89,7 +89,8 @@ def test_fanout_64_on_a_huge_row(oracle):
 
 @pytest.mark.parametrize("max_tickets", [1, 2, 4, 16, 64])
 def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
-    # tiny ticket budgets force several tiles per sampling ticket and 2..16 rounds per compaction tile
+    # tiny ticket budgets force several tiles of old rows per ticket and ranking tiles of up to 8 words per lane, each
+    # holding many batches of 256 new rows
     g = W.rmat_graph(600_000, 3_000_000, 17)
     feat = W.feature_table(600_000, 4, 2)
     og = to_host_graph(oracle, g)
@@ -99,8 +100,10 @@ def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
         plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (6, 5, 3), 40 + s, plan=plan, og=og,
                                          env=zg.make_envelope(zg.ENV_MAX, max_tickets=max_tickets))
     info = plan.info
-    assert info.grid_compact <= max(max_tickets, (600_000 // 32 + 16383) // 16384)
-    assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[2] // (256 * 4)))  # at most 4 tiles of 256 vertices per ticket
+    words = -(-600_000 // 32)
+    assert info.grid_compact <= max(max_tickets, -(-words // 8192))
+    # up to 256 old rows per ticket, ranking tiles of at most 8192 words
+    assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[1] // 256)) + max(max_tickets, -(-words // 8192))
 
 
 def test_randomised_configurations(oracle):

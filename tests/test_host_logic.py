@@ -98,8 +98,10 @@ def test_plan_query_max_envelope_is_eq1_hop_by_hop():
     assert list(info.edge_cap[:3]) == [500, 2400, 9000]
     assert info.envelope_bytes == info.maxsg_envelope_bytes
     assert info.workspace_bytes == info.envelope_bytes + info.scratch_bytes
-    assert info.scratch_bytes >= 10_000 * 4 + 10_000 // 8
-    assert list(info.grid_sample[:3]) == [1, 3, 12]  # tiles of 1024 / (lanes per vertex) = 128, 256, 256 vertices
+    assert info.scratch_bytes >= 10_000 * 4 + 3 * 10_000 // 8  # id map, two hop bitmaps, the "seen" bitmap
+    # hop-kernel launches: tickets for the rows of the previous frontier (tiles of 1024 / (lanes per row) = 128, 256, 256
+    # rows) plus ranking tiles over the 313 bitmap words (a power of two of words each, about one pass of new rows per tile)
+    assert list(info.grid_sample[:3]) == [1, 1 + 3, 3 + 10] and info.grid_compact == 10
 
 
 def test_plan_query_model_envelope_uses_margin_and_z():
@@ -234,6 +236,8 @@ def test_ticket_budget_is_an_envelope_field_not_an_environment_variable():
         del os.environ["ZG_MAX_TICKETS"]
     narrow = g.plan_query((5, 4, 3), 2000, zg.make_envelope(zg.ENV_MAX, max_tickets=2))
     assert narrow.grid_sample[2] < wide.grid_sample[2] and list(narrow.node_cap[:4]) == list(wide.node_cap[:4])
+    assert narrow.grid_sample[2] == 40 + 1  # 40 tickets of 256 old rows (a ticket holds 256 rows at most), one ranking tile
+    assert narrow.grid_sample[0] == 8 and wide.grid_sample[0] == 16  # 2000 seeds: tiles of 128 rows, two per ticket (256 rows) when the budget asks
 
 
 def test_the_binding_holds_none_of_the_envelope_arithmetic():
