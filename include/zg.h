@@ -67,6 +67,12 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
                                  reads 0.  A consumer kernel selects its inputs by that word: the host never looks at a
                                  flag.  zg_step_safe is refused on such a plan (ZG_ESTATE). */
 
+#define ZG_PLAN_X_ONE_PASS 32u /* the aggregation reads the feature table and writes the rows of X that belong to the last hop's
+                                 newly discovered vertices on the way; the gather copies the frontier's rows only */
+#define ZG_PLAN_X_TWO_PASS 64u /* the gather copies every row of S_{H-1}; the aggregation reads X.  With neither flag the
+                                 library picks by the size of the feature table (one pass from 4 GB on, rows of whole
+                                 128-byte lines); results are the same bytes either way */
+
 /* bits of the sticky device status word (zg_overflow_flag) */
 #define ZG_FLAG_HOP_OVERFLOW(h) (1u << (h)) /* |S_h| exceeded its cap at hop h: outputs of the step invalid */
 #define ZG_FLAG_SEED_RANGE (1u << 16)       /* a seed id outside [0, num_nodes) */
@@ -310,6 +316,12 @@ const char *zg_build_id(void);
  * aligned, device memory), one kernel on `stream`: it reads `bytes` and writes `bytes` of HBM, which calibrates
  * hardware traffic counters read for the library's other kernels.  Errors: ZG_EINVAL, ZG_EHIP. */
 int zg_calibration_copy(const void *d_src, void *d_dst, size_t bytes, void *stream);
+/* Re-enqueues one of the two feature launches of the plan's step on the state the last step left (section 2.2, "feature
+ * copy" and the first GraphSAGE aggregation), as the step runs them and without their small companion roles: which = 0
+ * the gather of the frontier's rows into X, which = 1 the mean aggregation that reads its input rows from the feature
+ * table and writes the remaining rows of X on the way.  Idempotent (the outputs are rewritten with the same values);
+ * meant for timing the step's dominant kernels one by one.  Errors: ZG_EINVAL, ZG_ESTATE (no features bound), ZG_EHIP. */
+int zg_plan_replay_features(zg_plan_t *p, int32_t which, void *stream);
 
 #ifdef __cplusplus
 }

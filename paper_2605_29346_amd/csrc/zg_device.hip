@@ -257,6 +257,8 @@ struct RelabelArgs {
     const int32_t *nbr;
     const int32_t *local_id;
     int32_t *col;
+    uint32_t *claim;   // last hop only: one bit per local id, set by the first edge that reaches a newly discovered vertex
+    uint8_t *own;      // ... and per edge, whether it was that edge
     uint32_t num_nodes;
     int32_t hop;
     uint32_t blocks; // workgroups given to this role (0: role absent)
@@ -264,6 +266,9 @@ struct RelabelArgs {
 
 // Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
 // Every sampled id is in S_h, so its map entry was written during this step (by the ingest or a ranking tile).
+// For the last hop the edges also settle who copies a newly discovered vertex's feature row into X: each such vertex is
+// claimed by whichever of its edges comes first (any one will do - they would all write the same row), so that the
+// aggregation, which reads the row anyway, is the only reader of it.
 // Works for any workgroup size; a workgroup covers kRelabelPerBlock edges.
 __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t block)
 {
@@ -271,10 +276,20 @@ __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t blo
     const uint32_t e0 = block * kRelabelPerBlock;
     if (e0 >= E) return;
     const uint32_t e1 = e0 + kRelabelPerBlock < E ? e0 + kRelabelPerBlock : E;
+    const int32_t n_front = a.own ? (int32_t)a.drmb->n[a.hop] : 0;
 #pragma unroll 4
     for (uint32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
         const int32_t g = a.nbr[e];
-        a.col[e] = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
+        const int32_t c = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
+        a.col[e] = c;
+        if (a.own) {
+            uint8_t mine = 0;
+            if (c >= n_front) {
+                const uint32_t bit = 1u << (c & 31);
+                mine = (atomicOr(&a.claim[(uint32_t)c >> 5], bit) & bit) ? 0 : 1;
+            }
+            a.own[e] = mine;
+        }
     }
 }
 
@@ -720,6 +735,8 @@ struct FinishArgs {
     uint32_t *log;
     uint64_t *status;       // the chained scans' status words of every launch: back to zero for the next step
     uint64_t status_words;
+    uint32_t *claim;        // the last hop's claim bits: back to zero as well
+    uint32_t claim_words;
     int32_t num_hops;
     uint32_t blocks; // workgroups given to this role (0: role absent)
 };
@@ -760,6 +777,7 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         if (g >= 0) a.seen[(uint32_t)g >> 5] = 0u;
     }
     for (uint64_t w = i; w < a.status_words; w += (uint64_t)a.blocks * kBlock) a.status[w] = 0ull;
+    for (uint32_t w = i; w < a.claim_words; w += a.blocks * kBlock) a.claim[w] = 0u;
     if (i == 0) {
         Drmb *d = a.drmb;
         for (int l = 0; l <= a.num_hops; ++l) d->ticket[l] = 0u;
@@ -792,6 +810,10 @@ struct RowArgs {
     const uint32_t *n_rows; // device address of the row count
     const uint32_t *n_cols; // aggregate: device address of the number of valid input rows, or null if `col_limit` holds it
     uint32_t col_limit;     // aggregate: number of valid input rows when n_cols is null (num_nodes for global ids)
+    float *x_dst;           // aggregate reading the table: X, whose rows of newly discovered vertices it writes on the way (or null)
+    const int32_t *x_row;   // ... per edge, the row of X (the local id)
+    const uint8_t *own;     // ... per edge, whether this edge is the one that writes it
+    int64_t ld_x;
     int64_t ld_src, ld_dst;
     uint64_t inv;
     uint32_t dimv;
@@ -869,12 +891,50 @@ __device__ __forceinline__ void gather_block(const RowArgs &a, uint32_t block, i
 // "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:].  A workgroup owns `rows` output
 // rows; their row_ptr slice and input-row indices are staged in LDS, then each lane owns one (row, 16-byte
 // column piece) pair at a time and accumulates over the row's edges in fp32, in edge order.
+// Inside a step the input rows are read from the feature table (addressed by the sampled global ids: feat[nbr_gid[e]]
+// is what X[col[e]] holds) and the rows of X that belong to the last hop's newly discovered vertices are written here,
+// by the edge that claimed the vertex: the row passes through the registers once instead of being copied by the
+// gather and read back from X (at one reference per row, a third less memory traffic for gather + aggregation).
+// the lanes' loop of the aggregation: one (row, 16-byte column piece) pair at a time.  ONE_PASS: the input rows come from
+// the feature table and are used once - loaded past the caches - and the edge that claimed a newly discovered vertex
+// copies the piece into X on the way
+template <int VEC, bool ONE_PASS>
+__device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, uint32_t rows, int32_t e_begin, uint32_t e_count,
+                                               const int32_t *s_rp, const int32_t *s_col, const int32_t *s_dst)
+{
+    typedef typename VecOf<VEC>::type T;
+    const uint32_t total = rows * a.dimv;
+    for (uint32_t e = threadIdx.x; e < total; e += kBlock) {
+        const uint32_t r = (uint32_t)(((uint64_t)e * a.inv) >> 32);
+        const uint32_t c = e - r * a.dimv;
+        const uint32_t b = (uint32_t)(s_rp[r] - e_begin);
+        uint32_t k = (uint32_t)(s_rp[r + 1] - s_rp[r]);
+        if (b + k > e_count) k = b < e_count ? e_count - b : 0;
+        T acc = VecOf<VEC>::zero();
+#pragma unroll 4
+        for (uint32_t j = 0; j < k; ++j) {
+            const int32_t cj = s_col[b + j];
+            if (cj >= 0) {
+                const T *src = reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
+                const T v = ONE_PASS ? __builtin_nontemporal_load(src) : *src;
+                acc += v;
+                if (ONE_PASS) {
+                    const int32_t dj = s_dst[b + j];
+                    if (dj >= 0) __builtin_nontemporal_store(v, reinterpret_cast<T *>(a.x_dst + (int64_t)dj * a.ld_x + (int64_t)c * VEC));
+                }
+            }
+        }
+        const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
+        *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
+    }
+}
+
 template <int VEC>
 __device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block, int32_t *s_mem)
 {
-    typedef typename VecOf<VEC>::type T;
     int32_t *s_rp = s_mem;               // [rows+1]
     int32_t *s_col = s_mem + a.rows + 1; // [rows * max_fanout]
+    int32_t *s_dst = s_col + a.rows * a.max_fanout; // [rows * max_fanout] when X is written on the way: row of X, or -1
     const uint32_t n = *a.n_rows;
     const uint32_t n_in = a.n_cols ? *a.n_cols : a.col_limit;
     const uint32_t row0 = block * a.rows;
@@ -888,24 +948,13 @@ __device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block
     for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) { // input row of every edge, -1 = none
         const uint32_t c = (uint32_t)a.col[e_begin + t];
         s_col[t] = c < n_in ? (int32_t)c : -1;
+        if (a.x_dst) s_dst[t] = (c < n_in && a.own[e_begin + t]) ? a.x_row[e_begin + t] : -1;
     }
     __syncthreads();
-    const uint32_t total = rows * a.dimv;
-    for (uint32_t e = threadIdx.x; e < total; e += kBlock) {
-        const uint32_t r = (uint32_t)(((uint64_t)e * a.inv) >> 32);
-        const uint32_t c = e - r * a.dimv;
-        const uint32_t b = (uint32_t)(s_rp[r] - e_begin);
-        uint32_t k = (uint32_t)(s_rp[r + 1] - s_rp[r]);
-        if (b + k > e_count) k = b < e_count ? e_count - b : 0;
-        T acc = VecOf<VEC>::zero();
-#pragma unroll 4
-        for (uint32_t j = 0; j < k; ++j) {
-            const int32_t cj = s_col[b + j];
-            if (cj >= 0) acc += *reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
-        }
-        const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
-        *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
-    }
+    if (a.x_dst)
+        aggregate_rows<VEC, true>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
+    else
+        aggregate_rows<VEC, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
 }
 
 // The two bandwidth-bound launches of a step, each with a small companion role on its last workgroups:
@@ -1124,6 +1173,8 @@ struct zg_plan_s {
     uint32_t *bitmap(int hop) const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap[hop & 1]); } // the one hop `hop` fills
     uint32_t *seen() const { return reinterpret_cast<uint32_t *>(ws + lay.off_seen); }
     uint64_t *status() const { return reinterpret_cast<uint64_t *>(ws + lay.off_status); }
+    uint32_t *claim() const { return reinterpret_cast<uint32_t *>(ws + lay.off_claim); }
+    uint8_t *own() const { return reinterpret_cast<uint8_t *>(ws + lay.off_own); }
     uint64_t *status_cnt(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_cnt[l]); }
     uint64_t *status_edge(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_edge[l]); }
 };
@@ -1148,6 +1199,22 @@ RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present, const zg_pla
     return ra;
 }
 
+// Whether the step's aggregation reads the feature table and writes the newly discovered vertices' rows of X on the way
+// ("one pass"), instead of the gather copying every row of S_{H-1} and the aggregation reading X ("two passes").
+// ZG_PLAN_FUSED_INPUT does not materialise those rows at all.  One pass moves up to a third less memory traffic, but it
+// scatters the writes of X over the aggregation's workgroups and reads rows from the table that two passes would find
+// in the 256 MB last-level cache (X of a mini-batch fits it, a feature table of gigabytes does not).  Measured on
+// MI355X: one pass wins at 56 GB of 512-byte rows (-6 % step time with four plans in flight), two passes win at
+// 0.6 - 1 GB tables and at rows that are not whole 128-byte lines.  Hence the rule; both flags override it.
+bool x_written_by_aggregation(const zg_plan_t *p)
+{
+    if (!p->d_feat || p->lay.feat_dim <= 0 || (p->flags & ZG_PLAN_FUSED_INPUT)) return false;
+    if (p->flags & ZG_PLAN_X_ONE_PASS) return true;
+    if (p->flags & ZG_PLAN_X_TWO_PASS) return false;
+    const uint64_t table_bytes = (uint64_t)p->graph->num_nodes * (uint64_t)p->ld_feat * 4u;
+    return table_bytes >= (4ull << 30) && (p->lay.ld_out * 4) % 128 == 0 && (p->ld_feat * 4) % 128 == 0;
+}
+
 FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate = nullptr, bool defer_completed = false)
 {
     FinishArgs fa;
@@ -1164,6 +1231,8 @@ FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate =
     fa.log = p->log();
     fa.status = p->status();
     fa.status_words = p->lay.status_words;
+    fa.claim = p->claim();
+    fa.claim_words = (uint32_t)p->lay.claim_words;
     fa.num_hops = H;
     fa.blocks = (uint32_t)((p->lay.node_cap[H - 1] + kBlock - 1) / kBlock);
     return fa;
@@ -1231,13 +1300,39 @@ int launch_aggregate(int vec, const RowArgs &agg, const FinishArgs &fa, hipStrea
 {
     const unsigned grid = agg.blocks + fa.blocks;
     if (grid == 0) return ZG_OK;
-    const size_t lds = agg.blocks ? ((size_t)agg.rows + 1 + (size_t)agg.rows * agg.max_fanout) * 4 : 0;
+    const size_t lds = agg.blocks ? ((size_t)agg.rows + 1 + (size_t)agg.rows * agg.max_fanout * (agg.x_dst ? 2 : 1)) * 4 : 0;
     if (vec == 4)
         hipLaunchKernelGGL(k_aggregate<4>, dim3(grid), dim3(kBlock), lds, st, agg, fa);
     else
         hipLaunchKernelGGL(k_aggregate<1>, dim3(grid), dim3(kBlock), lds, st, agg, fa);
     ZG_HIP(hipGetLastError());
     return ZG_OK;
+}
+
+// The step's two feature launches.  Two passes: the gather copies every row of S_{H-1} into X and the mean reads X.
+// One pass (and ZG_PLAN_FUSED_INPUT): the gather copies the rows of the frontier D_{H-1} only; the mean reads its input
+// rows from the table, addressed by the sampled global ids (feat[nbr_gid[e]] is the row X[col[e]] holds), and - unless
+// ZG_PLAN_FUSED_INPUT leaves them out - writes the other rows of X, those of the last hop's newly discovered
+// vertices, on the way.
+void step_feature_args(const zg_plan_t *p, RowArgs *gat, RowArgs *agg, int *vec)
+{
+    const Layout &L = p->lay;
+    const int H = L.num_hops;
+    *vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ld_out) && aligned16(p->agg(), L.ld_out) ? 4 : 1;
+    int v1 = *vec, v2 = *vec;
+    const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0, one_pass = x_written_by_aggregation(p);
+    if (fused || one_pass)
+        *agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ld_out, true, &v1);
+    else
+        *agg = aggregate_args(p, H - 1, p->X(), L.ld_out, L.feat_dim, p->agg(), L.ld_out, false, &v1);
+    if (one_pass) {
+        agg->x_dst = p->X();
+        agg->ld_x = L.ld_out;
+        agg->x_row = p->col(H - 1);
+        agg->own = p->own();
+    }
+    *gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, (fused || one_pass) ? H - 1 : H, &v2);
+    *vec = v1; // both tilings take the same vector width for the same dim and alignment
 }
 
 // a whole step, in order, on one stream (captured once, or issued eagerly): the hop kernel's launches 0..H, then the
@@ -1301,28 +1396,22 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
         ZG_HIP(hipGetLastError());
     }
     // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all
-    // four roles, the mean reading its rows from the table, was measured: no gain - the two big roles are bound
-    // by the same memory fabric.)
+    // four roles was measured: no gain - the two big roles are bound by the same memory fabric.)
     const bool feats = p->d_feat && L.feat_dim > 0;
     const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0;
     RowArgs agg, gat;
     std::memset(&agg, 0, sizeof(agg));
     std::memset(&gat, 0, sizeof(gat));
     int vec = 1;
-    if (feats) {
-        vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ld_out) && aligned16(p->agg(), L.ld_out) ? 4 : 1;
-        int v1 = vec, v2 = vec;
-        // ZG_PLAN_FUSED_INPUT: X stops at the frontier's rows, so the mean takes its input rows from the table,
-        // addressed by the sampled global ids (feat[nbr_gid[e]] is the row X[col[e]] would have held)
-        if (fused)
-            agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ld_out, true, &v1);
-        else
-            agg = aggregate_args(p, H - 1, p->X(), L.ld_out, L.feat_dim, p->agg(), L.ld_out, false, &v1);
-        gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, fused ? H - 1 : H, &v2);
-        vec = v1; // both tilings take the same vector width for the same dim and alignment
+    if (feats) step_feature_args(p, &gat, &agg, &vec);
+    RelabelArgs last = relabel_args(p, H - 1, true, gate);
+    if (x_written_by_aggregation(p)) {
+        last.claim = p->claim();
+        last.own = p->own();
     }
-    int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true, gate), st);
+    int rc = launch_gather(vec, gat, last, st);
     if (rc != ZG_OK) return rc;
+    (void)fused;
     return launch_aggregate(vec, agg, finish_args(p, true, gate, defer_completed), st);
 }
 
@@ -1400,6 +1489,7 @@ static int make_plan_object(zg_plan_t **out, const zg_graph_t *g, const Layout &
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[0], 0, (size_t)L.bitmap_words * 4, st);
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[1], 0, (size_t)L.bitmap_words * 4, st);
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
+        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_claim, 0, (size_t)L.claim_words * 4, st);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return bail(fail(ZG_EHIP, std::string("initialising the workspace: ") + hipGetErrorString(e)));
@@ -1425,8 +1515,9 @@ int zg_plan(zg_plan_t **out, const zg_graph_t *g, const int32_t *fanouts, int32_
     char *ws = static_cast<char *>(d_workspace);
     const bool with_twin = (env->flags & (ZG_PLAN_SAFE_TWIN | ZG_PLAN_AUTO_FALLBACK)) != 0;
     zg_plan_t *p = nullptr;
-    // with a twin the shared scratch is sized and cleared through the twin's (larger) layout
-    rc = make_plan_object(&p, g, L, env->flags, batch, ws, st, !with_twin);
+    // with a twin the shared scratch is sized through the twin's (larger) layout; each of the two clears the regions of
+    // its own layout (they overlap, but neither covers the other's: the gaps between one's regions are inside the other's)
+    rc = make_plan_object(&p, g, L, env->flags, batch, ws, st, true);
     if (rc != ZG_OK) return rc;
     if (with_twin) {
         rc = make_plan_object(&p->twin, g, Ls, env->flags & ~(ZG_PLAN_SAFE_TWIN | ZG_PLAN_AUTO_FALLBACK), batch, ws, st, true);
@@ -1550,6 +1641,19 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
         p->stepped = true;
     }
     return rc;
+}
+
+int zg_plan_replay_features(zg_plan_t *p, int32_t which, void *stream)
+{
+    if (!p) return fail(ZG_EINVAL, "null plan");
+    if (!p->d_feat || p->lay.feat_dim <= 0) return fail(ZG_ESTATE, "no feature table is bound to the plan");
+    if (which != 0 && which != 1) return fail(ZG_EINVAL, "which must be 0 (gather) or 1 (aggregation)");
+    RowArgs gat, agg;
+    int vec = 1;
+    step_feature_args(p, &gat, &agg, &vec);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (which == 0) return launch_gather(vec, gat, relabel_args(p, 0, false), st);
+    return launch_aggregate(vec, agg, finish_args(p, false), st);
 }
 
 int zg_pilot_update(const zg_plan_t *p, int64_t *largest, void *stream)

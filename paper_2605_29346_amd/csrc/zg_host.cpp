@@ -78,11 +78,13 @@ static void relocate(Layout &L, size_t env_base, size_t scratch_base)
         env(L.off_X);
         env(L.off_agg);
     }
+    env(L.off_own);
     scr(L.off_local_id);
     scr(L.off_bitmap[0]);
     scr(L.off_bitmap[1]);
     scr(L.off_seen);
     scr(L.off_status);
+    scr(L.off_claim);
     for (int l = 0; l <= L.num_hops; ++l) {
         scr(L.off_status_cnt[l]);
         scr(L.off_status_edge[l]);
@@ -195,6 +197,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
             b += align_up((size_t)(node_cap[h] + 1) * 4, kAlign) + kGuard;
             b += 2 * (align_up((size_t)node_cap[h] * fanouts[h] * 4, kAlign) + kGuard);
         }
+        b += align_up((size_t)node_cap[num_hops - 1] * fanouts[num_hops - 1], kAlign) + kGuard;
         if (feat_dim > 0 && fused) { // one matrix [X_self | mean]
             b += align_up((size_t)node_cap[num_hops - 1] * 2 * ldx * 4, kAlign) + kGuard;
         } else if (feat_dim > 0) {
@@ -277,6 +280,9 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_X = place((size_t)L.x_rows * ldx * 4);
         L.off_agg = place((size_t)L.node_cap[num_hops - 1] * ldx * 4);
     }
+    // per edge of the last hop: whether the edge claimed its (newly discovered) vertex.  Never cleared, so it sits with
+    // the plan's own buffers, not in the scratch a twin shares.
+    L.off_own = place((size_t)L.edge_cap[num_hops - 1]);
     L.envelope_end = off;
     L.off_local_id = place((size_t)V * 4);
     L.off_bitmap[0] = place((size_t)L.bitmap_words * 4); // the bitmap hop h fills is [h & 1]: launch h+1 ranks and clears it
@@ -292,6 +298,9 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_status_edge[l] = L.off_status + (w + n) * 8;
         w += 2 * n;
     }
+    // (zero between steps, like the status words: a plan and its twin lay their own scratch out over the same region)
+    L.claim_words = (size_t)(L.node_cap[num_hops] + 31) / 32;
+    L.off_claim = place(L.claim_words * 4);
     L.total = off;
 
     pi.envelope_bytes = (int64_t)L.envelope_end;

@@ -18,6 +18,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 I32, I64 = 0, 1
 GRAPH_VALIDATE = 1
 PLAN_EAGER, PLAN_REPLACE, PLAN_SAFE_TWIN, PLAN_FUSED_INPUT, PLAN_AUTO_FALLBACK = 1, 2, 4, 8, 16
+PLAN_X_ONE_PASS, PLAN_X_TWO_PASS = 32, 64
 ENV_MAX, ENV_MODEL, ENV_EXPLICIT, ENV_GRAPH = 0, 1, 2, 3
 FLAG_SEED_RANGE, FLAG_SEED_DUP, FLAG_INTERNAL = 1 << 16, 1 << 17, 1 << 18
 
@@ -33,7 +34,7 @@ EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_s
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
            "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
            "zg_step_status", "zg_envelope_model_graph", "zg_envelope_from_pilot", "zg_pilot_update", "zg_build_id",
-           "zg_calibration_copy", "zg_envelope_model_graph_static"]
+           "zg_calibration_copy", "zg_envelope_model_graph_static", "zg_plan_replay_features"]
 
 
 class Envelope(C.Structure):
@@ -120,6 +121,7 @@ def lib() -> C.CDLL:
         L.zg_envelope_from_pilot.argtypes = [P(i64), i32, dbl, u32, P(Envelope)]
         L.zg_pilot_update.argtypes = [vp, P(i64), vp]
         L.zg_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.zg_plan_replay_features.argtypes = [vp, i32, vp]
         for name in EXPORTS:
             if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile", "zg_build_id"):
                 getattr(L, name).restype = C.c_int
@@ -404,6 +406,10 @@ class Plan:
     def aggregate_mean(self, hop: int, x, out, stream=None) -> None:
         _check(lib().zg_aggregate_mean(self._h, hop, x.data_ptr(), x.stride(0), x.shape[1], out.data_ptr(),
                                        out.stride(0), _stream_ptr(stream)))
+
+    def replay_features(self, which: int, stream=None) -> None:
+        """Re-enqueue the step's gather (0) or aggregation (1) launch on the last step's state (for timing)."""
+        _check(lib().zg_plan_replay_features(self._h, which, _stream_ptr(stream)))
 
     def overflow_flag_ptr(self) -> int:
         p = C.c_void_p()

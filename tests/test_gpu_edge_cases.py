@@ -128,6 +128,7 @@ def test_randomised_configurations(oracle):
         og = to_host_graph(oracle, g)
         dg = zg.Graph(g.offsets.cuda(), g.indices.cuda(), validate=True)
         flags = (zg.PLAN_REPLACE if replace else 0) | (zg.PLAN_FUSED_INPUT if rnd.randint(3) == 0 else 0)
+        flags |= [0, zg.PLAN_X_ONE_PASS, zg.PLAN_X_TWO_PASS][int(rnd.randint(3))]  # who writes the new vertices' rows of X
         auto = mode == zg.ENV_MODEL and rnd.randint(2) == 0  # the twin's gated kernels redo an overflowed step
         flags |= zg.PLAN_AUTO_FALLBACK if auto else 0
         try:
