@@ -257,8 +257,6 @@ struct RelabelArgs {
     const int32_t *nbr;
     const int32_t *local_id;
     int32_t *col;
-    uint32_t *claim;   // last hop only: one bit per local id, set by the first edge that reaches a newly discovered vertex
-    uint8_t *own;      // ... and per edge, whether it was that edge
     uint32_t num_nodes;
     int32_t hop;
     uint32_t blocks; // workgroups given to this role (0: role absent)
@@ -266,9 +264,6 @@ struct RelabelArgs {
 
 // Hop h, "relabel edges": col[e] = local id of nbr_gid[e] (-1 for a vertex dropped by an overflow).
 // Every sampled id is in S_h, so its map entry was written during this step (by the ingest or a ranking tile).
-// For the last hop the edges also settle who copies a newly discovered vertex's feature row into X: each such vertex is
-// claimed by whichever of its edges comes first (any one will do - they would all write the same row), so that the
-// aggregation, which reads the row anyway, is the only reader of it.
 // Works for any workgroup size; a workgroup covers kRelabelPerBlock edges.
 __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t block)
 {
@@ -276,21 +271,114 @@ __device__ __forceinline__ void relabel_block(const RelabelArgs &a, uint32_t blo
     const uint32_t e0 = block * kRelabelPerBlock;
     if (e0 >= E) return;
     const uint32_t e1 = e0 + kRelabelPerBlock < E ? e0 + kRelabelPerBlock : E;
-    const int32_t n_front = a.own ? (int32_t)a.drmb->n[a.hop] : 0;
 #pragma unroll 4
     for (uint32_t e = e0 + threadIdx.x; e < e1; e += blockDim.x) {
         const int32_t g = a.nbr[e];
-        const int32_t c = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
-        a.col[e] = c;
-        if (a.own) {
-            uint8_t mine = 0;
-            if (c >= n_front) {
-                const uint32_t bit = 1u << (c & 31);
-                mine = (atomicOr(&a.claim[(uint32_t)c >> 5], bit) & bit) ? 0 : 1;
+        a.col[e] = (uint32_t)g < a.num_nodes ? a.local_id[g] : -1;
+    }
+}
+
+struct RowArgs {
+    const float *src;       // gather: feature table; aggregate: input rows
+    float *dst;
+    const int32_t *S;       // gather: global ids of the rows to copy
+    const int32_t *row_ptr; // aggregate
+    const int32_t *col;     // aggregate: per edge, the index of its input row (local ids, or global ids: see n_cols)
+    const uint32_t *n_rows; // device address of the row count
+    const uint32_t *n_cols; // aggregate: device address of the number of valid input rows, or null if `col_limit` holds it
+    uint32_t col_limit;     // aggregate: number of valid input rows when n_cols is null (num_nodes for global ids)
+    float *x_dst;           // aggregate reading the table: X, whose rows of newly discovered vertices it writes on the way (or null)
+    const int32_t *x_row;   // ... per edge, the row of X (the local id)
+    const uint8_t *own;     // ... per edge, whether this edge is the one that writes it
+    int64_t ld_x;
+    int64_t ld_src, ld_dst;
+    uint64_t inv;
+    uint32_t dimv;
+    uint32_t rows;
+    uint32_t max_fanout;
+    int32_t vec4;           // rows are moved in 16-byte pieces (else element by element)
+    const int32_t *local_id; // aggregate that relabels its block's edges itself: the id map ...
+    int32_t *col_out;        // ... and where col[e] = local id of nbr_gid[e] goes (null: `x_row` holds it already)
+    uint32_t blocks; // workgroups given to this role (0: role absent)
+};
+
+template <int VEC> struct VecOf;
+template <> struct VecOf<4> {
+    typedef v4f type;
+    static __device__ __forceinline__ v4f zero() { return (v4f){0.0f, 0.0f, 0.0f, 0.0f}; }
+};
+template <> struct VecOf<1> {
+    typedef float type;
+    static __device__ __forceinline__ float zero() { return 0.0f; }
+};
+
+// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
+// as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
+// fill every lane, four loads in flight per lane before the stores.
+template <int VEC, bool STREAM>
+__device__ __forceinline__ void gather_rows(const RowArgs &a, uint32_t row0, uint32_t rows, const int32_t *s_id)
+{
+    typedef typename VecOf<VEC>::type T;
+    const uint32_t total = rows * a.dimv;
+    for (uint32_t e0 = threadIdx.x; e0 < total; e0 += 4 * blockDim.x) {
+        T val[4];
+        uint32_t r[4], c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = e0 + u * blockDim.x;
+            if (e < total) {
+                r[u] = (uint32_t)(((uint64_t)e * a.inv) >> 32);
+                c[u] = e - r[u] * a.dimv;
+                const int32_t g = s_id[r[u]];
+                const T *src = reinterpret_cast<const T *>(a.src + (int64_t)g * a.ld_src + (int64_t)c[u] * VEC);
+                val[u] = g >= 0 ? (STREAM ? __builtin_nontemporal_load(src) : *src) : VecOf<VEC>::zero();
             }
-            a.own[e] = mine;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = e0 + u * blockDim.x;
+            if (e < total) {
+                T *dst = reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r[u]) * a.ld_dst + (int64_t)c[u] * VEC);
+                if (STREAM)
+                    __builtin_nontemporal_store(val[u], dst);
+                else
+                    *dst = val[u];
+            }
         }
     }
+}
+
+// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
+// as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
+// fill every lane, four loads in flight per lane before the stores.  When the gathered matrix of this step
+// is larger than the caches can hold for the aggregation that follows (decided on the device from the true
+// row count), loads and stores are non-temporal: measured +15 % at 200 MB, -10 % at 90 MB.
+// the same for a launch that copies the frontier's rows only (never large enough for the non-temporal path)
+template <int VEC>
+__device__ __forceinline__ void gather_rows_block(const RowArgs &a, uint32_t block, int32_t *s_id)
+{
+    const uint32_t n = *a.n_rows;
+    const uint32_t row0 = block * a.rows;
+    if (row0 >= n) return;
+    const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
+    if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
+    __syncthreads();
+    gather_rows<VEC, false>(a, row0, rows, s_id);
+}
+
+template <int VEC>
+__device__ __forceinline__ void gather_block(const RowArgs &a, uint32_t block, int32_t *s_id)
+{
+    const uint32_t n = *a.n_rows;
+    const uint32_t row0 = block * a.rows;
+    if (row0 >= n) return;
+    const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
+    if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
+    __syncthreads();
+    if ((uint64_t)n * a.dimv * (VEC * 4) > kGatherStreamBytes)
+        gather_rows<VEC, true>(a, row0, rows, s_id);
+    else
+        gather_rows<VEC, false>(a, row0, rows, s_id);
 }
 
 // Launch l = 0..H of the hop kernel: it samples hop l for the rows of D_l (l < H) and, for l > 0, first ranks the
@@ -308,6 +396,7 @@ struct HopArgs {
     uint32_t *seen;
     int32_t *row_ptr;         // block of hop l (launches 0..H-1)
     int32_t *nbr;
+    uint8_t *own;             // last hop, when the aggregation writes X: per edge, whether it was the first to reach its vertex
     uint64_t *status_cnt;     // chained scan over the launch's tickets: vertices ranked ...
     uint64_t *status_edge;    // ... and edges sampled
     uint32_t num_nodes;
@@ -392,7 +481,20 @@ __device__ __forceinline__ void sample_pass(const HopArgs &a, HopShared &sh, uin
                 if (old == (uint32_t)g) break;
                 h = (h + 1) & (kSampleHashSlots - 1);
             }
-            if (first) atomicOr(&a.bitmap_next[(uint32_t)g >> 5], 1u << (g & 31));
+            // The one atomic that finds the bit clear belongs to the first edge of the hop to reach the vertex.  For the last
+            // hop that edge is remembered: the aggregation reads the vertex's feature row for it anyway and, if the vertex
+            // turns out to be new, copies the row into X on the way (any one edge would do: they all carry the same row).
+            bool mine = false;
+            if (first) {
+                const uint32_t bit = 1u << (g & 31);
+                if (a.own)
+                    mine = (atomicOr(&a.bitmap_next[(uint32_t)g >> 5], bit) & bit) == 0u;
+                else
+                    atomicOr(&a.bitmap_next[(uint32_t)g >> 5], bit);
+            }
+            if (a.own) a.own[trp + (uint32_t)gl] = mine ? 1 : 0;
+        } else if (a.own) {
+            a.own[trp + (uint32_t)gl] = 0;
         }
     }
 }
@@ -452,7 +554,7 @@ __device__ __forceinline__ uint32_t lowest_set_bits(uint32_t x, uint32_t q)
 // to the cap.  Launch H ranks only.  The launch's surplus workgroups (the grid is sized by the caps) find no ticket
 // and return.
 template <typename OffT>
-__global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel, IngestArgs ing)
+__global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel, IngestArgs ing, RowArgs gat)
 {
     __shared__ HopShared sh;
     if (gate_closed(a.gate)) return;
@@ -460,8 +562,12 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
         const uint32_t b = blockIdx.x - a.blocks;
         if (b < rel.blocks)
             relabel_block(rel, b);
-        else
+        else if (b < rel.blocks + ing.blocks)
             ingest_block(ing, b - rel.blocks, sh.in);
+        else if (gat.vec4) // the closing launch may carry the copy of the frontier's feature rows (their ids are final by now)
+            gather_rows_block<4>(gat, b - rel.blocks - ing.blocks, sh.v);
+        else
+            gather_rows_block<1>(gat, b - rel.blocks - ing.blocks, sh.v);
         return;
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -735,8 +841,6 @@ struct FinishArgs {
     uint32_t *log;
     uint64_t *status;       // the chained scans' status words of every launch: back to zero for the next step
     uint64_t status_words;
-    uint32_t *claim;        // the last hop's claim bits: back to zero as well
-    uint32_t claim_words;
     int32_t num_hops;
     uint32_t blocks; // workgroups given to this role (0: role absent)
 };
@@ -777,7 +881,6 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
         if (g >= 0) a.seen[(uint32_t)g >> 5] = 0u;
     }
     for (uint64_t w = i; w < a.status_words; w += (uint64_t)a.blocks * kBlock) a.status[w] = 0ull;
-    for (uint32_t w = i; w < a.claim_words; w += a.blocks * kBlock) a.claim[w] = 0u;
     if (i == 0) {
         Drmb *d = a.drmb;
         for (int l = 0; l <= a.num_hops; ++l) d->ticket[l] = 0u;
@@ -799,93 +902,6 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
             __hip_atomic_store(&a.mailbox->completed, epoch + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         if (a.gate) publish_gate_owner(a);
     }
-}
-
-struct RowArgs {
-    const float *src;       // gather: feature table; aggregate: input rows
-    float *dst;
-    const int32_t *S;       // gather: global ids of the rows to copy
-    const int32_t *row_ptr; // aggregate
-    const int32_t *col;     // aggregate: per edge, the index of its input row (local ids, or global ids: see n_cols)
-    const uint32_t *n_rows; // device address of the row count
-    const uint32_t *n_cols; // aggregate: device address of the number of valid input rows, or null if `col_limit` holds it
-    uint32_t col_limit;     // aggregate: number of valid input rows when n_cols is null (num_nodes for global ids)
-    float *x_dst;           // aggregate reading the table: X, whose rows of newly discovered vertices it writes on the way (or null)
-    const int32_t *x_row;   // ... per edge, the row of X (the local id)
-    const uint8_t *own;     // ... per edge, whether this edge is the one that writes it
-    int64_t ld_x;
-    int64_t ld_src, ld_dst;
-    uint64_t inv;
-    uint32_t dimv;
-    uint32_t rows;
-    uint32_t max_fanout;
-    uint32_t blocks; // workgroups given to this role (0: role absent)
-};
-
-template <int VEC> struct VecOf;
-template <> struct VecOf<4> {
-    typedef v4f type;
-    static __device__ __forceinline__ v4f zero() { return (v4f){0.0f, 0.0f, 0.0f, 0.0f}; }
-};
-template <> struct VecOf<1> {
-    typedef float type;
-    static __device__ __forceinline__ float zero() { return 0.0f; }
-};
-
-// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
-// as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
-// fill every lane, four loads in flight per lane before the stores.
-template <int VEC, bool STREAM>
-__device__ __forceinline__ void gather_rows(const RowArgs &a, uint32_t row0, uint32_t rows, const int32_t *s_id)
-{
-    typedef typename VecOf<VEC>::type T;
-    const uint32_t total = rows * a.dimv;
-    for (uint32_t e0 = threadIdx.x; e0 < total; e0 += 4 * kBlock) {
-        T val[4];
-        uint32_t r[4], c[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t e = e0 + u * kBlock;
-            if (e < total) {
-                r[u] = (uint32_t)(((uint64_t)e * a.inv) >> 32);
-                c[u] = e - r[u] * a.dimv;
-                const int32_t g = s_id[r[u]];
-                const T *src = reinterpret_cast<const T *>(a.src + (int64_t)g * a.ld_src + (int64_t)c[u] * VEC);
-                val[u] = g >= 0 ? (STREAM ? __builtin_nontemporal_load(src) : *src) : VecOf<VEC>::zero();
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t e = e0 + u * kBlock;
-            if (e < total) {
-                T *dst = reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r[u]) * a.ld_dst + (int64_t)c[u] * VEC);
-                if (STREAM)
-                    __builtin_nontemporal_store(val[u], dst);
-                else
-                    *dst = val[u];
-            }
-        }
-    }
-}
-
-// "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
-// as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
-// fill every lane, four loads in flight per lane before the stores.  When the gathered matrix of this step
-// is larger than the caches can hold for the aggregation that follows (decided on the device from the true
-// row count), loads and stores are non-temporal: measured +15 % at 200 MB, -10 % at 90 MB.
-template <int VEC>
-__device__ __forceinline__ void gather_block(const RowArgs &a, uint32_t block, int32_t *s_id)
-{
-    const uint32_t n = *a.n_rows;
-    const uint32_t row0 = block * a.rows;
-    if (row0 >= n) return;
-    const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
-    if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
-    __syncthreads();
-    if ((uint64_t)n * a.dimv * (VEC * 4) > kGatherStreamBytes)
-        gather_rows<VEC, true>(a, row0, rows, s_id);
-    else
-        gather_rows<VEC, false>(a, row0, rows, s_id);
 }
 
 // "Mean-aggregate": out[i,:] = (1/k_i) * sum over row i of in[col[e],:].  A workgroup owns `rows` output
@@ -947,8 +963,17 @@ __device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block
     if (e_count > a.rows * a.max_fanout) e_count = a.rows * a.max_fanout;
     for (uint32_t t = threadIdx.x; t < e_count; t += kBlock) { // input row of every edge, -1 = none
         const uint32_t c = (uint32_t)a.col[e_begin + t];
-        s_col[t] = c < n_in ? (int32_t)c : -1;
-        if (a.x_dst) s_dst[t] = (c < n_in && a.own[e_begin + t]) ? a.x_row[e_begin + t] : -1;
+        const bool valid = c < n_in;
+        s_col[t] = valid ? (int32_t)c : -1;
+        int32_t lid = -1;
+        if (a.col_out) { // "relabel edges" of this block, done here: c is the sampled global id
+            lid = valid ? a.local_id[c] : -1;
+            a.col_out[e_begin + t] = lid;
+        } else if (a.x_dst) {
+            lid = a.x_row[e_begin + t];
+        }
+        // the hop's first edge to a vertex writes its row of X, if the vertex is new (the frontier's rows are the gather's)
+        if (a.x_dst) s_dst[t] = (valid && a.own[e_begin + t] && lid >= (int32_t)n) ? lid : -1;
     }
     __syncthreads();
     if (a.x_dst)
@@ -965,10 +990,11 @@ __global__ __launch_bounds__(kBlock) void k_gather(RowArgs gat, RelabelArgs last
 {
     extern __shared__ int32_t s_mem[];
     if (gate_closed(last.gate)) return;
-    if (blockIdx.x < gat.blocks)
-        gather_block<VEC>(gat, blockIdx.x, s_mem);
+    // the relabel's workgroups come first: their chains of dependent loads then run under the copy instead of after it
+    if (blockIdx.x < last.blocks)
+        relabel_block(last, blockIdx.x);
     else
-        relabel_block(last, blockIdx.x - gat.blocks);
+        gather_block<VEC>(gat, blockIdx.x - last.blocks, s_mem);
 }
 
 template <int VEC>
@@ -1173,7 +1199,6 @@ struct zg_plan_s {
     uint32_t *bitmap(int hop) const { return reinterpret_cast<uint32_t *>(ws + lay.off_bitmap[hop & 1]); } // the one hop `hop` fills
     uint32_t *seen() const { return reinterpret_cast<uint32_t *>(ws + lay.off_seen); }
     uint64_t *status() const { return reinterpret_cast<uint64_t *>(ws + lay.off_status); }
-    uint32_t *claim() const { return reinterpret_cast<uint32_t *>(ws + lay.off_claim); }
     uint8_t *own() const { return reinterpret_cast<uint8_t *>(ws + lay.off_own); }
     uint64_t *status_cnt(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_cnt[l]); }
     uint64_t *status_edge(int l) const { return reinterpret_cast<uint64_t *>(ws + lay.off_status_edge[l]); }
@@ -1231,8 +1256,6 @@ FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate =
     fa.log = p->log();
     fa.status = p->status();
     fa.status_words = p->lay.status_words;
-    fa.claim = p->claim();
-    fa.claim_words = (uint32_t)p->lay.claim_words;
     fa.num_hops = H;
     fa.blocks = (uint32_t)((p->lay.node_cap[H - 1] + kBlock - 1) / kBlock);
     return fa;
@@ -1321,18 +1344,29 @@ void step_feature_args(const zg_plan_t *p, RowArgs *gat, RowArgs *agg, int *vec)
     *vec = aligned16(p->d_feat, p->ld_feat) && aligned16(p->X(), L.ld_out) && aligned16(p->agg(), L.ld_out) ? 4 : 1;
     int v1 = *vec, v2 = *vec;
     const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0, one_pass = x_written_by_aggregation(p);
-    if (fused || one_pass)
+    if (fused || one_pass) {
         *agg = aggregate_args(p, H - 1, p->d_feat, p->ld_feat, L.feat_dim, p->agg(), L.ld_out, true, &v1);
-    else
+        // the aggregation relabels the last hop's edges itself (it holds their sampled ids anyway): no launch in between
+        agg->local_id = p->local_id();
+        agg->col_out = p->col(H - 1);
+    } else {
         *agg = aggregate_args(p, H - 1, p->X(), L.ld_out, L.feat_dim, p->agg(), L.ld_out, false, &v1);
+    }
     if (one_pass) {
         agg->x_dst = p->X();
         agg->ld_x = L.ld_out;
-        agg->x_row = p->col(H - 1);
         agg->own = p->own();
     }
     *gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, (fused || one_pass) ? H - 1 : H, &v2);
     *vec = v1; // both tilings take the same vector width for the same dim and alignment
+    gat->vec4 = agg->vec4 = *vec == 4 ? 1 : 0;
+}
+
+// whether the step has no gather launch of its own: the frontier's rows are copied by workgroups of the closing hop-kernel
+// launch and the aggregation relabels the last hop's edges itself (H+2 launches per step)
+bool features_ride_along(const zg_plan_t *p)
+{
+    return p->d_feat && p->lay.feat_dim > 0 && ((p->flags & ZG_PLAN_FUSED_INPUT) || x_written_by_aggregation(p));
 }
 
 // a whole step, in order, on one stream (captured once, or issued eagerly): the hop kernel's launches 0..H, then the
@@ -1343,6 +1377,14 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
     const Layout &L = p->lay;
     const zg_graph_t *g = p->graph;
     const int H = L.num_hops;
+    const bool feats = p->d_feat && L.feat_dim > 0;
+    const bool ride = features_ride_along(p);
+    RowArgs agg, gat, no_rows;
+    std::memset(&agg, 0, sizeof(agg));
+    std::memset(&gat, 0, sizeof(gat));
+    std::memset(&no_rows, 0, sizeof(no_rows));
+    int vec = 1;
+    if (feats) step_feature_args(p, &gat, &agg, &vec);
     for (int l = 0; l <= H; ++l) {
         HopArgs ha;
         std::memset(&ha, 0, sizeof(ha));
@@ -1358,6 +1400,7 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
         ha.seen = p->seen();
         ha.row_ptr = l < H ? p->row_ptr(l) : nullptr;
         ha.nbr = l < H ? p->nbr(l) : nullptr;
+        ha.own = (l == H - 1 && x_written_by_aggregation(p)) ? p->own() : nullptr;
         ha.status_cnt = p->status_cnt(l);
         ha.status_edge = p->status_edge(l);
         ha.num_nodes = (uint32_t)g->num_nodes;
@@ -1388,30 +1431,27 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
             ia.num_nodes = (uint32_t)g->num_nodes;
             ia.blocks = (uint32_t)((p->batch + kHopBlock - 1) / kHopBlock);
         }
-        const unsigned grid = ha.blocks + ra.blocks + ia.blocks;
+        // the closing launch can carry the copy of the frontier's rows: D_{H-1} is final since launch H-1 (a workgroup
+        // of 1024 lanes takes four times the rows of the 256-lane gather, 256 at most: its ids sit in the LDS row slots)
+        RowArgs ga = no_rows;
+        if (l == H && ride) {
+            ga = gat;
+            ga.rows = std::min<uint32_t>(kHopRows, gat.rows * (kHopBlock / kBlock));
+            ga.blocks = (uint32_t)((L.node_cap[H - 1] + ga.rows - 1) / ga.rows);
+        }
+        const unsigned grid = ha.blocks + ra.blocks + ia.blocks + ga.blocks;
         if (g->offsets_dtype == ZG_I64)
-            hipLaunchKernelGGL(k_hop<int64_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia);
+            hipLaunchKernelGGL(k_hop<int64_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
         else
-            hipLaunchKernelGGL(k_hop<int32_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia);
+            hipLaunchKernelGGL(k_hop<int32_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
         ZG_HIP(hipGetLastError());
     }
-    // the tail: {gather + relabel of the last hop}, then {aggregation + end-of-step clean-up}.  (One launch for all
-    // four roles was measured: no gain - the two big roles are bound by the same memory fabric.)
-    const bool feats = p->d_feat && L.feat_dim > 0;
-    const bool fused = (p->flags & ZG_PLAN_FUSED_INPUT) != 0;
-    RowArgs agg, gat;
-    std::memset(&agg, 0, sizeof(agg));
-    std::memset(&gat, 0, sizeof(gat));
-    int vec = 1;
-    if (feats) step_feature_args(p, &gat, &agg, &vec);
-    RelabelArgs last = relabel_args(p, H - 1, true, gate);
-    if (x_written_by_aggregation(p)) {
-        last.claim = p->claim();
-        last.own = p->own();
+    // the tail: {gather + relabel of the last hop} - unless both ride along elsewhere -, then {aggregation + end-of-step
+    // clean-up}.  (One launch for all four roles was measured: no gain - the two big roles are bound by the same memory fabric.)
+    if (!ride) {
+        int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true, gate), st);
+        if (rc != ZG_OK) return rc;
     }
-    int rc = launch_gather(vec, gat, last, st);
-    if (rc != ZG_OK) return rc;
-    (void)fused;
     return launch_aggregate(vec, agg, finish_args(p, true, gate, defer_completed), st);
 }
 
@@ -1489,7 +1529,6 @@ static int make_plan_object(zg_plan_t **out, const zg_graph_t *g, const Layout &
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[0], 0, (size_t)L.bitmap_words * 4, st);
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_bitmap[1], 0, (size_t)L.bitmap_words * 4, st);
         if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_status, 0, L.status_words * 8, st);
-        if (e == hipSuccess) e = hipMemsetAsync(p->ws + L.off_claim, 0, (size_t)L.claim_words * 4, st);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return bail(fail(ZG_EHIP, std::string("initialising the workspace: ") + hipGetErrorString(e)));

@@ -84,7 +84,6 @@ static void relocate(Layout &L, size_t env_base, size_t scratch_base)
     scr(L.off_bitmap[1]);
     scr(L.off_seen);
     scr(L.off_status);
-    scr(L.off_claim);
     for (int l = 0; l <= L.num_hops; ++l) {
         scr(L.off_status_cnt[l]);
         scr(L.off_status_edge[l]);
@@ -280,8 +279,8 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_X = place((size_t)L.x_rows * ldx * 4);
         L.off_agg = place((size_t)L.node_cap[num_hops - 1] * ldx * 4);
     }
-    // per edge of the last hop: whether the edge claimed its (newly discovered) vertex.  Never cleared, so it sits with
-    // the plan's own buffers, not in the scratch a twin shares.
+    // per edge of the last hop: whether the edge was the hop's first to reach its vertex (the aggregation's cue to copy
+    // the vertex's row into X).  Not zero between steps, so it sits with the plan's own buffers, not in the scratch a twin shares.
     L.off_own = place((size_t)L.edge_cap[num_hops - 1]);
     L.envelope_end = off;
     L.off_local_id = place((size_t)V * 4);
@@ -298,9 +297,6 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         L.off_status_edge[l] = L.off_status + (w + n) * 8;
         w += 2 * n;
     }
-    // (zero between steps, like the status words: a plan and its twin lay their own scratch out over the same region)
-    L.claim_words = (size_t)(L.node_cap[num_hops] + 31) / 32;
-    L.off_claim = place(L.claim_words * 4);
     L.total = off;
 
     pi.envelope_bytes = (int64_t)L.envelope_end;

@@ -66,8 +66,7 @@ struct Layout {
     size_t off_X = 0, off_agg = 0;
     size_t envelope_end = 0;
     size_t off_local_id = 0, off_bitmap[2] = {}, off_seen = 0, off_status = 0;
-    size_t off_claim = 0, off_own = 0; // last hop: claim bit per local id, "this edge claimed its vertex" byte per edge
-    size_t claim_words = 0;
+    size_t off_own = 0; // last hop: per edge, whether it was the hop's first edge to reach its vertex
     size_t status_words = 0; // uint64 words: per launch, one vertex-count chain and one edge-count chain over its tickets
     size_t off_status_cnt[ZG_MAX_HOPS + 1] = {}, off_status_edge[ZG_MAX_HOPS + 1] = {};
     size_t total = 0;
