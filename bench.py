@@ -170,28 +170,33 @@ def summarize_kernel(argv) -> None:
     trace = list(csv.DictReader(open(os.path.join(args.folder, f"{args.prefix}_kernel_trace.csv"))))
     ours = [r for r in trace if "zg::" in r["Kernel_Name"] and "k_calibrate_copy" not in r["Kernel_Name"]]
     ours.sort(key=lambda r: int(r["Start_Timestamp"]))
-    # a step starts with its first-hop sampling launch (the kernel that also ingests the seeds) or, in older traces, k_ingest
-    first_kernel = "k_ingest" if any("k_ingest" in r["Kernel_Name"] for r in ours) else "k_sample_first"
-    ingest = [i for i, r in enumerate(ours) if first_kernel in r["Kernel_Name"]]
+    # every step ends with one k_aggregate launch (its last workgroups close the step); the profiled loop holds nothing else
+    steps = sum(1 for r in ours if "k_aggregate" in r["Kernel_Name"])
     print("# rocprofv3 kernel-trace summary")
     if args.cmd:
         print(f"\ncommand: `{args.cmd}`")
     if args.note:
         print(f"\n{args.note}")
-    print(f"\nkernel dispatches of the library: {len(ours)}; steps: {len(ingest)}")
+    print(f"\nkernel dispatches of the library: {len(ours)}; steps: {steps}")
 
     seg = None
-    if len(ingest) > args.skip_steps + 1:
-        first = ingest[args.skip_steps]
-        # steady-state window: from the first counted step's first kernel to the end of the last step (stand-alone
-        # kernel launches after the last step are not part of the loop)
-        last = ingest[-1]
-        per_step = -(-(ingest[-1] - first) // (len(ingest) - 1 - args.skip_steps))
-        seg = ours[first: last + per_step]
+    per_step = len(ours) // steps if steps else 0
+    if steps > args.skip_steps + 1 and per_step * steps == len(ours):
+        # steady-state window: the dispatches after the warm-up steps' share (with several plans in flight the steps
+        # interleave, so the cut is by dispatch count, in start order)
+        seg = ours[args.skip_steps * per_step:]
+    ingest = list(range(steps))
+
+    def label(r):
+        # the hop kernel's launches of a step share a name: tell them apart by their grid (workgroups of 1024 lanes)
+        name = _short(r["Kernel_Name"])
+        if "k_hop" in name and r.get("Grid_Size_X") and r.get("Workgroup_Size_X"):
+            name += f" [{int(r['Grid_Size_X']) // int(r['Workgroup_Size_X'])} workgroups]"
+        return name
 
     stats = defaultdict(list)
     for r in (seg if (args.window_only and seg) else ours):
-        stats[_short(r["Kernel_Name"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        stats[label(r)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
     total = sum(sum(v) for v in stats.values())
     where = f"the {len(ingest) - args.skip_steps} steps after the first {args.skip_steps}" if (args.window_only and seg) else "the whole run"
     print(f"\nper-kernel durations over {where}:")
@@ -459,18 +464,29 @@ def main():
     t_gather = time_kernel(lambda: plan.replay_features(0))
     t_agg = time_kernel(lambda: plan.replay_features(1))
     n_new = nH - nHm1
-    bytes_gather = nHm1 * (4 + 2 * 4 * cfg.dim)
-    csr = EHm1 * (4 + 4 + 1) + (nHm1 + 1) * 4  # sampled ids, local ids, claim flags, row_ptr
-    bytes_agg = n_new * 4 * cfg.dim * 2 + nHm1 * 4 * cfg.dim + csr  # every new vertex's row read once and written once, the means written
-    bytes_agg_noreuse = EHm1 * 4 * cfg.dim + n_new * 4 * cfg.dim + nHm1 * 4 * cfg.dim + csr  # every edge fetches its row
+    one_pass = bool(plan.out.x_one_pass)
+    row = 4 * cfg.dim
+    if one_pass:
+        # the gather copies the frontier's rows; the aggregation reads every new vertex's row at least once and writes it
+        # into X (rows of frontier vertices that are sampled again are not counted), and writes the means
+        gather_rows = nHm1
+        csr = EHm1 * (4 + 4 + 1) + (nHm1 + 1) * 4  # sampled ids, local ids (written here), first-edge flags, row_ptr
+        bytes_agg = n_new * row * 2 + nHm1 * row + csr
+        bytes_agg_noreuse = EHm1 * row + n_new * row + nHm1 * row + csr  # every edge fetches its row
+    else:
+        # the gather copies every row of S_{H-1}; the aggregation reads every row of X at least once and writes the means
+        gather_rows = nH
+        csr = EHm1 * 4 + (nHm1 + 1) * 4
+        bytes_agg = nH * row + nHm1 * row + csr
+        bytes_agg_noreuse = EHm1 * row + nHm1 * row + csr
+    bytes_gather = gather_rows * (4 + 2 * row)
     kernels = {
         "gather": {"seconds": t_gather, "bytes": bytes_gather, "GBps": bytes_gather / t_gather / 1e9,
-                   "name": "k_gather", "rows": nHm1},
-        # `bytes` is the compulsory figure (every new vertex's row read once; rows of frontier vertices that are sampled
-        # again are not counted); without cache reuse every edge fetches its row
+                   "name": "k_gather", "rows": gather_rows},
+        # `bytes` is the compulsory figure; without cache reuse every edge fetches its row
         "aggregate": {"seconds": t_agg, "bytes": bytes_agg, "GBps": bytes_agg / t_agg / 1e9, "name": "k_aggregate",
                       "bytes_without_reuse": bytes_agg_noreuse, "GBps_without_reuse": bytes_agg_noreuse / t_agg / 1e9,
-                      "rows_read_per_edge": EHm1, "x_rows_written": n_new},
+                      "rows_read_per_edge": EHm1, "x_rows_written": n_new if one_pass else 0},
     }
     dom = max(kernels, key=lambda k: kernels[k]["seconds"])
     roofline = {"bound": "hbm", "kernel": kernels[dom]["name"], "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
@@ -484,6 +500,8 @@ def main():
     two_pass_bytes = nH * (4 + 2 * 4 * cfg.dim) + nH * 4 * cfg.dim + EHm1 * 4 + (nHm1 + 1) * 4 + nHm1 * 4 * cfg.dim
     stage = {"gather_plus_aggregate_GBps": stage_bytes / (t_gather + t_agg) / 1e9,
              "frac_of_peak": stage_bytes / (t_gather + t_agg) / 1e9 / HBM_PEAK_GBS,
+             "features": "one pass (aggregation reads the table, writes the new vertices' rows of X)" if one_pass else
+                         "two passes (gather copies every row, aggregation reads X)",
              "two_pass_bytes": two_pass_bytes, "two_pass_equivalent_GBps": two_pass_bytes / (t_gather + t_agg) / 1e9,
              "share_of_single_stream_step": (t_gather + t_agg) / (wall_single / K)}
 

@@ -151,6 +151,10 @@ typedef struct {
     int64_t x_row_cap;       /* rows of d_X: node_cap[H], or node_cap[H-1] with ZG_PLAN_FUSED_INPUT (rows i < n_{H-1} are valid) */
     const uint32_t *d_active; /* ZG_PLAN_AUTO_FALLBACK: 1 if the last step fell back to the twin (its outputs are the valid
                                  ones), else 0; always 0 on other plans */
+    int32_t x_one_pass;       /* 1 if, with the feature table bound at the time of the call, the step's aggregation reads the
+                                 table and writes the new vertices' rows of X on the way (ZG_PLAN_X_ONE_PASS or the automatic
+                                 choice), 0 if the gather copies every row and the aggregation reads X */
+    int32_t reserved;
 } zg_outputs;
 
 /* Fixed text for a zg_status / thread-local detail of the calling thread's last failure.  Both return

@@ -927,18 +927,29 @@ __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, 
         uint32_t k = (uint32_t)(s_rp[r + 1] - s_rp[r]);
         if (b + k > e_count) k = b < e_count ? e_count - b : 0;
         T acc = VecOf<VEC>::zero();
-#pragma unroll 4
-        for (uint32_t j = 0; j < k; ++j) {
-            const int32_t cj = s_col[b + j];
-            if (cj >= 0) {
-                const T *src = reinterpret_cast<const T *>(a.src + (int64_t)cj * a.ld_src + (int64_t)c * VEC);
-                const T v = ONE_PASS ? __builtin_nontemporal_load(src) : *src;
-                acc += v;
-                if (ONE_PASS) {
-                    const int32_t dj = s_dst[b + j];
-                    if (dj >= 0) __builtin_nontemporal_store(v, reinterpret_cast<T *>(a.x_dst + (int64_t)dj * a.ld_x + (int64_t)c * VEC));
+        // eight of the row's edges at a time: all their loads are in flight before the first is added (in edge order)
+        for (uint32_t j0 = 0; j0 < k; j0 += 8) {
+            int32_t cj[8];
+            T v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) cj[u] = j0 + u < k ? s_col[b + j0 + u] : -1;
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                v[u] = VecOf<VEC>::zero();
+                if (cj[u] >= 0) {
+                    const T *src = reinterpret_cast<const T *>(a.src + (int64_t)cj[u] * a.ld_src + (int64_t)c * VEC);
+                    v[u] = ONE_PASS ? __builtin_nontemporal_load(src) : *src;
                 }
             }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u)
+                if (cj[u] >= 0) {
+                    acc += v[u];
+                    if (ONE_PASS) { // the hop's first edge to a new vertex copies the piece into X on the way
+                        const int32_t dj = s_dst[b + j0 + u];
+                        if (dj >= 0) __builtin_nontemporal_store(v[u], reinterpret_cast<T *>(a.x_dst + (int64_t)dj * a.ld_x + (int64_t)c * VEC));
+                    }
+                }
         }
         const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
         *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
@@ -1645,6 +1656,7 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
     o->d_epoch = &p->drmb()->epoch;
     o->x_row_cap = L.x_rows;
     o->d_active = &p->drmb()->active;
+    o->x_one_pass = x_written_by_aggregation(p) ? 1 : 0;
     return ZG_OK;
 }
 

@@ -66,7 +66,7 @@ class Outputs(C.Structure):
                 ("node_cap", C.c_int64 * (MAX_HOPS + 1)), ("edge_cap", C.c_int64 * MAX_HOPS),
                 ("d_X", C.c_void_p), ("ldx", C.c_int64), ("d_agg", C.c_void_p), ("ld_agg", C.c_int64),
                 ("d_log", C.c_void_p), ("log_capacity", C.c_int32), ("d_epoch", C.c_void_p), ("x_row_cap", C.c_int64),
-                ("d_active", C.c_void_p)]
+                ("d_active", C.c_void_p), ("x_one_pass", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None
@@ -375,6 +375,7 @@ class Plan:
         assert feat.is_cuda and feat.dtype == torch.float32 and feat.dim() == 2 and feat.stride(1) == 1
         self.features = feat
         _check(lib().zg_plan_bind_features(self._h, feat.data_ptr(), feat.stride(0)))
+        _check(lib().zg_plan_outputs(self._h, C.byref(self.out)))  # (which kernel writes X depends on the table)
 
     def step(self, seeds, rng_key: int, stream=None) -> None:
         """Enqueue one mini-batch (seeds: int32 CUDA tensor of `batch` distinct ids); returns at once."""

@@ -2,9 +2,10 @@
 benchmark times (hipGraph replays issued back to back, no host sync in between).
 
 For every configuration a run of consecutive steps is enqueued; the device-side log must match the
-checker's sizes for every step, and for selected steps (the plan is re-run on them) every output is
-compared element by element: ids, relabel maps, block CSR bit-exact, gathered rows bit-exact, mean
-aggregation within 1e-5.  The feature table of the largest configuration never exists on the host:
+checker's sizes for every step.  Then, untimed, every step is run again one at a time and its ids, relabel
+maps and block CSR are compared element by element (bit-exact); on a spread of steps also the gathered
+rows (bit-exact) and the mean aggregation (within 1e-5).  The batch-size and depth sweep points of the
+paper's evaluation are covered the same way.  The feature table of the largest configuration never exists on the host:
 its rows are regenerated from the procedural definition for the vertices a step touched.
 """
 import os
@@ -28,7 +29,10 @@ def _need_gpu():
     zg.lib()
 
 
-def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True, graph_aware=False):
+def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True, graph_aware=False, every_step=None):
+    """`steps` steps back to back (sizes of every step against the checker through the device log), then a second,
+    untimed pass that steps one at a time: ids, relabel maps and block CSR of EVERY step of `every_step` (default: all)
+    bit-exact, and on the steps of `full_steps` also the gathered rows bit-exact and the aggregation within 1e-5."""
     t0 = time.time()
     g = cfg.build_graph(device="cuda")
     feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device="cuda")
@@ -48,6 +52,7 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
     log = plan.view_log().cpu().numpy()
     flags = int(plan.view_counts()[3].cpu()[0]) & 0xFFFFFFFF
     assert flags == 0, f"status flags {flags:#x}"
+    every_step = range(steps) if every_step is None else every_step
     refs = {}
     for s in range(steps):
         ref = og.sample_blocks(batches[s].cpu().numpy(), cfg.fanouts, cfg.key_for(s))
@@ -55,14 +60,17 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
         assert rec[0] == s and rec[1] == 0
         assert list(rec[2:2 + H + 1]) == ref.n, f"step {s}: n {list(rec[2:2 + H + 1])} != {ref.n}"
         assert list(rec[2 + H + 1:2 + 2 * H + 1]) == ref.E, f"step {s}: E"
-        if s in full_steps:
+        if s in full_steps or s in every_step:
             refs[s] = ref
     feat_host = feat.cpu().numpy() if table_on_host else None
     worst = 0.0
     for s, ref in refs.items():
         plan.step(batches[s], cfg.key_for(s))
-        res = plan.read_step()
+        full = s in full_steps
+        res = plan.read_step(with_features=full)
         compare_blocks(res, ref, f"{cfg.name}/step{s}")
+        if not full:
+            continue
         if feat_host is not None:
             X_ref = oracle.gather(feat_host, ref.S)
         else:
@@ -73,22 +81,23 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
         assert e <= AGG_RTOL, f"{cfg.name}/step{s}: aggregation error {e}"
         worst = max(worst, e)
         print(f"[{cfg.name}] step {s}: n={ref.n} E={ref.E} agg err {e:.2e}", flush=True)
+    print(f"[{cfg.name}] ids, relabel maps and block CSR of {len(refs)} steps bit-exact; features of {len(full_steps)} steps", flush=True)
     return plan, worst
 
 
 def test_medium_dense_full_size(oracle):
     cfg = W.CONFIGS["medium_dense"]
-    _run_config(oracle, cfg, steps=120, full_steps={0, 57, 119})
+    _run_config(oracle, cfg, steps=120, full_steps={0, 19, 38, 57, 76, 95, 119})
 
 
 def test_large_sparse_full_size(oracle):
     cfg = W.CONFIGS["large_sparse"]
-    _run_config(oracle, cfg, steps=60, full_steps={0, 33})
+    _run_config(oracle, cfg, steps=60, full_steps={0, 11, 22, 33, 44, 59})
 
 
 def test_envelope_stress_full_size(oracle):
     cfg = W.CONFIGS["envelope_stress"]
-    _run_config(oracle, cfg, steps=60, full_steps={0, 41})
+    _run_config(oracle, cfg, steps=60, full_steps={0, 13, 27, 41, 59})
 
 
 def test_envelope_stress_on_the_graph_aware_envelope(oracle):
@@ -106,7 +115,23 @@ def test_very_large_full_size(oracle):
     if total < 150 * 2**30:
         pytest.skip("needs a GPU with at least 150 GiB")
     cfg = W.CONFIGS["very_large"]
-    _run_config(oracle, cfg, steps=6, full_steps={0, 5}, table_on_host=False)
+    _run_config(oracle, cfg, steps=6, full_steps={0, 1, 2, 3, 4, 5}, table_on_host=False)
+
+
+@pytest.mark.parametrize("batch", [64, 4096])
+def test_batch_sweep_points_on_the_medium_dense_graph(oracle, batch):
+    # the paper's batch-size sweep (section 5.4) runs 64 .. 4096 seeds on its Reddit setting: both ends, element by element
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["medium_dense"], batch=batch)
+    _run_config(oracle, cfg, steps=12, full_steps={0, 11}, env_mode=zg.ENV_MODEL)
+
+
+@pytest.mark.parametrize("fanouts", [(25, 10, 10), (25, 10, 10, 10, 10)])
+def test_depth_sweep_points_on_the_medium_dense_graph(oracle, fanouts):
+    # the paper's depth sweep (section 5.4): three and five hops, element by element
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["medium_dense"], fanouts=fanouts)
+    _run_config(oracle, cfg, steps=6, full_steps={0, 5}, env_mode=zg.ENV_MODEL)
 
 
 def test_long_pipelined_run_matches_the_checker_step_by_step(oracle):
