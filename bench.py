@@ -467,11 +467,12 @@ def main():
     one_pass = bool(plan.out.x_one_pass)
     row = 4 * cfg.dim
     if one_pass:
-        # the gather copies the frontier's rows; the aggregation reads every new vertex's row at least once and writes it
-        # into X (rows of frontier vertices that are sampled again are not counted), and writes the means
+        # the gather copies the frontier's rows; the aggregation reads every distinct row its edges point to at least once
+        # (counted exactly, from the last step's block), writes the new vertices' rows into X, and writes the means
         gather_rows = nHm1
+        distinct = int(torch.unique(plan.view_block(H - 1)[1][:EHm1]).numel())
         csr = EHm1 * (4 + 4 + 1) + (nHm1 + 1) * 4  # sampled ids, local ids (written here), first-edge flags, row_ptr
-        bytes_agg = n_new * row * 2 + nHm1 * row + csr
+        bytes_agg = distinct * row + n_new * row + nHm1 * row + csr
         bytes_agg_noreuse = EHm1 * row + n_new * row + nHm1 * row + csr  # every edge fetches its row
     else:
         # the gather copies every row of S_{H-1}; the aggregation reads every row of X at least once and writes the means
