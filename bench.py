@@ -97,7 +97,10 @@ def summarize_pmc(argv) -> None:
             if "k_calibrate_copy" in name:
                 calib.append(val)
             elif "zg::" in name:
-                per_kernel[_short(name)].append(val)
+                label = _short(name)
+                if "k_hop" in label and r.get("Grid_Size") and r.get("Workgroup_Size"):  # a step's hop launches, told apart by grid
+                    label += f"[{int(r['Grid_Size']) // int(r['Workgroup_Size'])}wg]"
+                per_kernel[label].append(val)
         return per_kernel, calib
 
     fetch, fcal = load(args.fetch_csv, "FETCH_SIZE")
@@ -120,7 +123,7 @@ def summarize_pmc(argv) -> None:
         w = write.get(k, [0.0])[-args.last:]
         fb, wb = f_unit * sum(f) / len(f), w_unit * sum(w) / len(w)
         print(f"| {k} | {len(f)} | {sum(f) / len(f):.1f} | {sum(w) / len(w):.1f} | {fb / 1e6:.2f} | {wb / 1e6:.2f} |")
-        lines.append(f"{k.split('<')[0]} {fb:.0f} {wb:.0f}")
+        lines.append(f"{k.split('<')[0] + (k[k.index('['):] if '[' in k else '')} {fb:.0f} {wb:.0f}")
     if args.traffic_out:
         with open(args.traffic_out, "w") as fh:
             fh.write("# kernel  hbm_read_bytes_per_launch  hbm_write_bytes_per_launch  (from the summary beside this file)\n")
