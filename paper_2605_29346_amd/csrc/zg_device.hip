@@ -1674,7 +1674,6 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     p->mailbox->slot[slot].key = rng_key;
     std::atomic_thread_fence(std::memory_order_seq_cst);
     p->issued += 1;
-    reinterpret_cast<std::atomic<uint32_t> *>(&p->mailbox->issued)->store(p->issued, std::memory_order_release); // the slot is filled
     int rc = ZG_OK;
     if (p->flags & ZG_PLAN_EAGER) {
         rc = enqueue_step(p, st);
@@ -1686,8 +1685,9 @@ int zg_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream
     }
     if (rc != ZG_OK) {
         p->issued -= 1; // nothing was enqueued: the slot is free again
-        reinterpret_cast<std::atomic<uint32_t> *>(&p->mailbox->issued)->store(p->issued, std::memory_order_release);
     } else {
+        // only now may an earlier step copy the slot ahead of time: a slot whose launch failed is filled again later
+        reinterpret_cast<std::atomic<uint32_t> *>(&p->mailbox->issued)->store(p->issued, std::memory_order_release);
         p->last_stream = st;
         p->stepped = true;
     }
