@@ -115,7 +115,7 @@ def test_very_large_full_size(oracle):
     if total < 150 * 2**30:
         pytest.skip("needs a GPU with at least 150 GiB")
     cfg = W.CONFIGS["very_large"]
-    _run_config(oracle, cfg, steps=6, full_steps={0, 1, 2, 3, 4, 5}, table_on_host=False)
+    _run_config(oracle, cfg, steps=30, full_steps={0, 5, 11, 17, 23, 29}, table_on_host=False)
 
 
 @pytest.mark.parametrize("batch", [64, 4096])
