@@ -68,10 +68,10 @@ enum zg_dtype { ZG_I32 = 0, ZG_I64 = 1 };
                                  flag.  zg_step_safe is refused on such a plan (ZG_ESTATE). */
 
 #define ZG_PLAN_X_ONE_PASS 32u /* the aggregation reads the feature table and writes the rows of X that belong to the last hop's
-                                 newly discovered vertices on the way; the gather copies the frontier's rows only */
-#define ZG_PLAN_X_TWO_PASS 64u /* the gather copies every row of S_{H-1}; the aggregation reads X.  With neither flag the
-                                 library picks by the size of the feature table (one pass from 4 GB on, rows of whole
-                                 128-byte lines); results are the same bytes either way */
+                                 newly discovered vertices on the way; the gather copies the frontier's rows only.  This is
+                                 what a plan does by default; the flag is kept for callers that state it */
+#define ZG_PLAN_X_TWO_PASS 64u /* the gather copies every row of S_{H-1}; the aggregation reads X.  Results are the same
+                                 bytes either way */
 
 /* bits of the sticky device status word (zg_overflow_flag) */
 #define ZG_FLAG_HOP_OVERFLOW(h) (1u << (h)) /* |S_h| exceeded its cap at hop h: outputs of the step invalid */
@@ -152,8 +152,8 @@ typedef struct {
     const uint32_t *d_active; /* ZG_PLAN_AUTO_FALLBACK: 1 if the last step fell back to the twin (its outputs are the valid
                                  ones), else 0; always 0 on other plans */
     int32_t x_one_pass;       /* 1 if, with the feature table bound at the time of the call, the step's aggregation reads the
-                                 table and writes the new vertices' rows of X on the way (ZG_PLAN_X_ONE_PASS or the automatic
-                                 choice), 0 if the gather copies every row and the aggregation reads X */
+                                 table and writes the new vertices' rows of X on the way (the default), 0 if the gather copies every
+                                 row and the aggregation reads X (ZG_PLAN_X_TWO_PASS, or ZG_PLAN_FUSED_INPUT) */
     int32_t reserved;
 } zg_outputs;
 

@@ -297,6 +297,7 @@ struct RowArgs {
     uint32_t rows;
     uint32_t max_fanout;
     int32_t vec4;           // rows are moved in 16-byte pieces (else element by element)
+    int32_t nt;             // aggregate writing X: table rows and X rows go past the caches (non-temporal)
     const int32_t *local_id; // aggregate that relabels its block's edges itself: the id map ...
     int32_t *col_out;        // ... and where col[e] = local id of nbr_gid[e] goes (null: `x_row` holds it already)
     uint32_t blocks; // workgroups given to this role (0: role absent)
@@ -912,9 +913,9 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
 // by the edge that claimed the vertex: the row passes through the registers once instead of being copied by the
 // gather and read back from X (at one reference per row, a third less memory traffic for gather + aggregation).
 // the lanes' loop of the aggregation: one (row, 16-byte column piece) pair at a time.  ONE_PASS: the input rows come from
-// the feature table and are used once - loaded past the caches - and the edge that claimed a newly discovered vertex
-// copies the piece into X on the way
-template <int VEC, bool ONE_PASS>
+// the feature table and the edge that claimed a newly discovered vertex copies the piece into X on the way.  NT: the
+// table is far larger than the last-level cache, so its rows are used once - loaded, and X stored, past the caches
+template <int VEC, bool ONE_PASS, bool NT>
 __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, uint32_t rows, int32_t e_begin, uint32_t e_count,
                                                const int32_t *s_rp, const int32_t *s_col, const int32_t *s_dst)
 {
@@ -938,7 +939,7 @@ __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, 
                 v[u] = VecOf<VEC>::zero();
                 if (cj[u] >= 0) {
                     const T *src = reinterpret_cast<const T *>(a.src + (int64_t)cj[u] * a.ld_src + (int64_t)c * VEC);
-                    v[u] = ONE_PASS ? __builtin_nontemporal_load(src) : *src;
+                    v[u] = NT ? __builtin_nontemporal_load(src) : *src;
                 }
             }
 #pragma unroll
@@ -947,7 +948,13 @@ __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, 
                     acc += v[u];
                     if (ONE_PASS) { // the hop's first edge to a new vertex copies the piece into X on the way
                         const int32_t dj = s_dst[b + j0 + u];
-                        if (dj >= 0) __builtin_nontemporal_store(v[u], reinterpret_cast<T *>(a.x_dst + (int64_t)dj * a.ld_x + (int64_t)c * VEC));
+                        if (dj >= 0) {
+                            T *xd = reinterpret_cast<T *>(a.x_dst + (int64_t)dj * a.ld_x + (int64_t)c * VEC);
+                            if (NT)
+                                __builtin_nontemporal_store(v[u], xd);
+                            else
+                                *xd = v[u];
+                        }
                     }
                 }
         }
@@ -987,10 +994,12 @@ __device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block
         if (a.x_dst) s_dst[t] = (valid && a.own[e_begin + t] && lid >= (int32_t)n) ? lid : -1;
     }
     __syncthreads();
-    if (a.x_dst)
-        aggregate_rows<VEC, true>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
+    if (a.x_dst && a.nt)
+        aggregate_rows<VEC, true, true>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
+    else if (a.x_dst)
+        aggregate_rows<VEC, true, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
     else
-        aggregate_rows<VEC, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
+        aggregate_rows<VEC, false, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
 }
 
 // The two bandwidth-bound launches of a step, each with a small companion role on its last workgroups:
@@ -1237,16 +1246,22 @@ RelabelArgs relabel_args(const zg_plan_t *p, int hop, bool present, const zg_pla
 
 // Whether the step's aggregation reads the feature table and writes the newly discovered vertices' rows of X on the way
 // ("one pass"), instead of the gather copying every row of S_{H-1} and the aggregation reading X ("two passes").
-// ZG_PLAN_FUSED_INPUT does not materialise those rows at all.  One pass moves up to a third less memory traffic, but it
-// scatters the writes of X over the aggregation's workgroups and reads rows from the table that two passes would find
-// in the 256 MB last-level cache (X of a mini-batch fits it, a feature table of gigabytes does not).  Measured on
-// MI355X: one pass wins at 56 GB of 512-byte rows (-6 % step time with four plans in flight), two passes win at
-// 0.6 - 1 GB tables and at rows that are not whole 128-byte lines.  Hence the rule; both flags override it.
+// ZG_PLAN_FUSED_INPUT does not materialise those rows at all.  One pass moves up to a third less memory traffic and has
+// one launch fewer.  Measured on MI355X against two passes (step time on one stream / with four plans in flight):
+// 56 GB table of 512-byte rows -6 % with four plans; 0.6 GB table of 2400-byte rows -7 % / -3 %; 1 GB of 400-byte rows
+// -4 % / 0; 1 GB of 1 KB rows 0 / -1 %.  Hence one pass unless the flag asks for two.
 bool x_written_by_aggregation(const zg_plan_t *p)
 {
     if (!p->d_feat || p->lay.feat_dim <= 0 || (p->flags & ZG_PLAN_FUSED_INPUT)) return false;
-    if (p->flags & ZG_PLAN_X_ONE_PASS) return true;
-    if (p->flags & ZG_PLAN_X_TWO_PASS) return false;
+    return (p->flags & ZG_PLAN_X_TWO_PASS) == 0;
+}
+
+// One pass, past the caches or through them: a table of many GB leaves nothing of use in the 256 MB last-level cache, so
+// its rows are loaded and X is stored non-temporally (at 56 GB: 222 instead of 242 us per step) - if rows are whole
+// 128-byte lines, a non-temporal store of part of a line being a read-modify-write in memory.  Smaller tables keep
+// their hot rows in the caches (at 0.6 - 1 GB the non-temporal variant is 4 - 10 % slower than two passes).
+bool one_pass_streams(const zg_plan_t *p)
+{
     const uint64_t table_bytes = (uint64_t)p->graph->num_nodes * (uint64_t)p->ld_feat * 4u;
     return table_bytes >= (4ull << 30) && (p->lay.ld_out * 4) % 128 == 0 && (p->ld_feat * 4) % 128 == 0;
 }
@@ -1367,6 +1382,7 @@ void step_feature_args(const zg_plan_t *p, RowArgs *gat, RowArgs *agg, int *vec)
         agg->x_dst = p->X();
         agg->ld_x = L.ld_out;
         agg->own = p->own();
+        agg->nt = one_pass_streams(p) ? 1 : 0;
     }
     *gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, (fused || one_pass) ? H - 1 : H, &v2);
     *vec = v1; // both tilings take the same vector width for the same dim and alignment
