@@ -29,35 +29,53 @@ def _need_gpu():
     zg.lib()
 
 
-def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True, graph_aware=False, every_step=None):
-    """`steps` steps back to back (sizes of every step against the checker through the device log), then a second,
-    untimed pass that steps one at a time: ids, relabel maps and block CSR of EVERY step of `every_step` (default: all)
-    bit-exact, and on the steps of `full_steps` also the gathered rows bit-exact and the aggregation within 1e-5."""
+def _build(oracle, cfg):
     t0 = time.time()
     g = cfg.build_graph(device="cuda")
     feat = W.feature_table(g.num_nodes, cfg.dim, cfg.feat_seed, device="cuda")
     torch.cuda.synchronize()
     print(f"\n[{cfg.name}] |V|={g.num_nodes} |E|={g.num_edges} built in {time.time() - t0:.1f}s", flush=True)
-    og = to_host_graph(oracle, g)
+    return g, feat, to_host_graph(oracle, g)
+
+
+def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on_host=True, graph_aware=False, every_step=None,
+                pipeline=1, built=None):
+    """`steps` steps back to back - on `pipeline` plans and streams, issued round-robin as the benchmark does - with the
+    sizes of every step against the checker through the device logs; then a second, untimed pass that steps one at a
+    time: ids, relabel maps and block CSR of EVERY step of `every_step` (default: all) bit-exact, and on the steps of
+    `full_steps` also the gathered rows bit-exact and the aggregation within 1e-5."""
+    g, feat, og = built if built is not None else _build(oracle, cfg)
     pool = cfg.seed_pool(g)
     dg = zg.Graph(g.offsets, g.indices)
     env = zg.graph_envelope(dg, cfg.fanouts, cfg.batch, seed_prob=pool.seed_prob(g.num_nodes)) if graph_aware else zg.make_envelope(env_mode)
-    plan = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
-    plan.bind_features(feat)
+    P = pipeline
+    plans, streams = [], []
+    for _ in range(P):
+        p = zg.Plan(dg, cfg.fanouts, cfg.batch, env, feat_dim=cfg.dim)
+        p.bind_features(feat)
+        plans.append(p)
+        streams.append(zg.new_stream() if P > 1 else None)
+    plan = plans[0]
     H = len(cfg.fanouts)
     batches = [pool.batch_for(s).contiguous() for s in range(steps)]
-    for s in range(steps):
-        plan.step(batches[s], cfg.key_for(s))
     torch.cuda.synchronize()
-    log = plan.view_log().cpu().numpy()
-    flags = int(plan.view_counts()[3].cpu()[0]) & 0xFFFFFFFF
-    assert flags == 0, f"status flags {flags:#x}"
+    for s in range(steps):
+        if P > 1:
+            plans[s % P].step(batches[s], cfg.key_for(s), streams[s % P])
+        else:
+            plan.step(batches[s], cfg.key_for(s))
+    torch.cuda.synchronize()
+    logs = [p.view_log().cpu().numpy() for p in plans]
+    for p in plans:
+        flags = int(p.view_counts()[3].cpu()[0]) & 0xFFFFFFFF
+        assert flags == 0, f"status flags {flags:#x}"
     every_step = range(steps) if every_step is None else every_step
     refs = {}
     for s in range(steps):
         ref = og.sample_blocks(batches[s].cpu().numpy(), cfg.fanouts, cfg.key_for(s))
-        rec = log[s % log.shape[0]]
-        assert rec[0] == s and rec[1] == 0
+        log = logs[s % P]
+        rec = log[(s // P) % log.shape[0]]
+        assert rec[0] == s // P and rec[1] == 0
         assert list(rec[2:2 + H + 1]) == ref.n, f"step {s}: n {list(rec[2:2 + H + 1])} != {ref.n}"
         assert list(rec[2 + H + 1:2 + 2 * H + 1]) == ref.E, f"step {s}: E"
         if s in full_steps or s in every_step:
@@ -65,9 +83,14 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
     feat_host = feat.cpu().numpy() if table_on_host else None
     worst = 0.0
     for s, ref in refs.items():
-        plan.step(batches[s], cfg.key_for(s))
+        q = plans[s % P]
+        if P > 1:
+            q.step(batches[s], cfg.key_for(s), streams[s % P])
+        else:
+            q.step(batches[s], cfg.key_for(s))
+        torch.cuda.synchronize()
         full = s in full_steps
-        res = plan.read_step(with_features=full)
+        res = q.read_step(with_features=full)
         compare_blocks(res, ref, f"{cfg.name}/step{s}")
         if not full:
             continue
@@ -81,7 +104,9 @@ def _run_config(oracle, cfg, *, steps, full_steps, env_mode=zg.ENV_MAX, table_on
         assert e <= AGG_RTOL, f"{cfg.name}/step{s}: aggregation error {e}"
         worst = max(worst, e)
         print(f"[{cfg.name}] step {s}: n={ref.n} E={ref.E} agg err {e:.2e}", flush=True)
-    print(f"[{cfg.name}] ids, relabel maps and block CSR of {len(refs)} steps bit-exact; features of {len(full_steps)} steps", flush=True)
+    print(f"[{cfg.name}] {P} plan(s): ids, relabel maps and block CSR of {len(refs)} steps bit-exact; features of {len(full_steps)} steps", flush=True)
+    for p in plans[1:]:
+        p.close()
     return plan, worst
 
 
@@ -115,7 +140,13 @@ def test_very_large_full_size(oracle):
     if total < 150 * 2**30:
         pytest.skip("needs a GPU with at least 150 GiB")
     cfg = W.CONFIGS["very_large"]
-    _run_config(oracle, cfg, steps=30, full_steps={0, 5, 11, 17, 23, 29}, table_on_host=False)
+    built = _build(oracle, cfg)
+    # the benchmark's own launch configuration: the model's envelope, four plans on four streams
+    plan, _ = _run_config(oracle, cfg, steps=32, full_steps={0, 5, 10, 15, 22, 31}, env_mode=zg.ENV_MODEL, table_on_host=False, pipeline=4,
+                          built=built)
+    plan.close()
+    # and the worst-case envelope (other tile sizes, other launch grids) on one stream
+    _run_config(oracle, cfg, steps=8, full_steps={0, 7}, table_on_host=False, built=built)
 
 
 @pytest.mark.parametrize("batch", [64, 4096])
