@@ -297,7 +297,7 @@ struct RowArgs {
     uint32_t rows;
     uint32_t max_fanout;
     int32_t vec4;           // rows are moved in 16-byte pieces (else element by element)
-    int32_t nt;             // aggregate writing X: table rows and X rows go past the caches (non-temporal)
+    int32_t nt;             // aggregate writing X: the rows of X are stored past the caches (non-temporal)
     const int32_t *local_id; // aggregate that relabels its block's edges itself: the id map ...
     int32_t *col_out;        // ... and where col[e] = local id of nbr_gid[e] goes (null: `x_row` holds it already)
     uint32_t blocks; // workgroups given to this role (0: role absent)
@@ -913,8 +913,9 @@ __device__ __forceinline__ void finish_block(const FinishArgs &a, uint32_t block
 // by the edge that claimed the vertex: the row passes through the registers once instead of being copied by the
 // gather and read back from X (at one reference per row, a third less memory traffic for gather + aggregation).
 // the lanes' loop of the aggregation: one (row, 16-byte column piece) pair at a time.  ONE_PASS: the input rows come from
-// the feature table and the edge that claimed a newly discovered vertex copies the piece into X on the way.  NT: the
-// table is far larger than the last-level cache, so its rows are used once - loaded, and X stored, past the caches
+// the feature table and the edge that claimed a newly discovered vertex copies the piece into X on the way.  NT: X is
+// stored past the caches (nothing reads it again within the step); the table's rows are loaded through them, so that a
+// row several edges share comes from memory once
 template <int VEC, bool ONE_PASS, bool NT>
 __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, uint32_t rows, int32_t e_begin, uint32_t e_count,
                                                const int32_t *s_rp, const int32_t *s_col, const int32_t *s_dst)
@@ -939,7 +940,7 @@ __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, 
                 v[u] = VecOf<VEC>::zero();
                 if (cj[u] >= 0) {
                     const T *src = reinterpret_cast<const T *>(a.src + (int64_t)cj[u] * a.ld_src + (int64_t)c * VEC);
-                    v[u] = NT ? __builtin_nontemporal_load(src) : *src;
+                    v[u] = *src;
                 }
             }
 #pragma unroll
@@ -1256,14 +1257,15 @@ bool x_written_by_aggregation(const zg_plan_t *p)
     return (p->flags & ZG_PLAN_X_TWO_PASS) == 0;
 }
 
-// One pass, past the caches or through them: a table of many GB leaves nothing of use in the 256 MB last-level cache, so
-// its rows are loaded and X is stored non-temporally (at 56 GB: 222 instead of 242 us per step) - if rows are whole
-// 128-byte lines, a non-temporal store of part of a line being a read-modify-write in memory.  Smaller tables keep
-// their hot rows in the caches (at 0.6 - 1 GB the non-temporal variant is 4 - 10 % slower than two passes).
+// One pass: how the rows move.  The table's rows are loaded through the caches - about a fifth of the last hop's edges
+// lead to a vertex another edge leads to as well, and its row is then found in the last-level cache instead of in HBM.
+// The rows of X are stored non-temporally when rows are whole 128-byte lines (a non-temporal store of part of a line is a
+// read-modify-write in memory).  Measured at a 56 GB table of 512-byte rows, step time with four plans in flight / on one
+// stream: loads and stores non-temporal 191 / 222 us, loads cached and stores non-temporal 183 / 227 us, both cached
+// 194 / 242 us; at a 1 GB table of 1 KB rows: both cached 78.8 / 108.7 us, loads cached and stores non-temporal 76.2 / 109.1 us.
 bool one_pass_streams(const zg_plan_t *p)
 {
-    const uint64_t table_bytes = (uint64_t)p->graph->num_nodes * (uint64_t)p->ld_feat * 4u;
-    return table_bytes >= (4ull << 30) && (p->lay.ld_out * 4) % 128 == 0 && (p->ld_feat * 4) % 128 == 0;
+    return (p->lay.ld_out * 4) % 128 == 0;
 }
 
 FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate = nullptr, bool defer_completed = false)
