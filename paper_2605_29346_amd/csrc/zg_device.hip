@@ -297,7 +297,7 @@ struct RowArgs {
     uint32_t rows;
     uint32_t max_fanout;
     int32_t vec4;           // rows are moved in 16-byte pieces (else element by element)
-    int32_t nt;             // aggregate writing X: the rows of X are stored past the caches (non-temporal)
+    int32_t nt;             // aggregate inside a step: what it writes (means, rows of X) is stored past the caches (non-temporal)
     const int32_t *local_id; // aggregate that relabels its block's edges itself: the id map ...
     int32_t *col_out;        // ... and where col[e] = local id of nbr_gid[e] goes (null: `x_row` holds it already)
     uint32_t blocks; // workgroups given to this role (0: role absent)
@@ -364,12 +364,7 @@ __device__ __forceinline__ void gather_rows_block(const RowArgs &a, uint32_t blo
     const uint32_t rows = n - row0 < a.rows ? n - row0 : a.rows;
     if (threadIdx.x < rows) s_id[threadIdx.x] = a.S[row0 + threadIdx.x];
     __syncthreads();
-    // nothing in the step reads these rows of X again: they are stored past the caches when rows are whole 128-byte lines
-    // (measured with the rows of 512 bytes and 1 KB: 2 - 3 % of the step)
-    if ((a.ld_dst * 4) % 128 == 0 && (a.dimv * VEC * 4) % 128 == 0)
-        gather_rows<VEC, false, true>(a, row0, rows, s_id);
-    else
-        gather_rows<VEC, false>(a, row0, rows, s_id);
+    gather_rows<VEC, false, true>(a, row0, rows, s_id); // nothing in the step reads these rows of X again: stored past the caches
 }
 
 template <int VEC>
@@ -1004,10 +999,10 @@ __device__ __forceinline__ void aggregate_block(const RowArgs &a, uint32_t block
         if (a.x_dst) s_dst[t] = (valid && a.own[e_begin + t] && lid >= (int32_t)n) ? lid : -1;
     }
     __syncthreads();
-    if (a.x_dst && a.nt)
+    if (a.x_dst)
         aggregate_rows<VEC, true, true>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
-    else if (a.x_dst)
-        aggregate_rows<VEC, true, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
+    else if (a.nt)
+        aggregate_rows<VEC, false, true>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
     else
         aggregate_rows<VEC, false, false>(a, row0, rows, e_begin, e_count, s_rp, s_col, s_dst);
 }
@@ -1266,16 +1261,14 @@ bool x_written_by_aggregation(const zg_plan_t *p)
     return (p->flags & ZG_PLAN_X_TWO_PASS) == 0;
 }
 
-// One pass: how the rows move.  The table's rows are loaded through the caches - about a fifth of the last hop's edges
-// lead to a vertex another edge leads to as well, and its row is then found in the last-level cache instead of in HBM.
-// The rows of X are stored non-temporally when rows are whole 128-byte lines (a non-temporal store of part of a line is a
-// read-modify-write in memory).  Measured at a 56 GB table of 512-byte rows, step time with four plans in flight / on one
-// stream: loads and stores non-temporal 191 / 222 us, loads cached and stores non-temporal 183 / 227 us, both cached
-// 194 / 242 us; at a 1 GB table of 1 KB rows: both cached 78.8 / 108.7 us, loads cached and stores non-temporal 76.2 / 109.1 us.
-bool one_pass_streams(const zg_plan_t *p)
-{
-    return (p->lay.ld_out * 4) % 128 == 0;
-}
+// One pass (and ZG_PLAN_FUSED_INPUT): how the rows move.  The table's rows are loaded through the caches - about a fifth of
+// the last hop's edges lead to a vertex another edge leads to as well, and its row is then found in the last-level cache
+// instead of in HBM.  What the feature launches write - the frontier's rows of X, the new vertices' rows of X, the rows of
+// means - nothing in the step reads again: it is stored non-temporally, whatever the row length (rows that are not whole
+// 128-byte lines gain as much: 2400-byte rows 84 -> 71 us per step with four plans in flight, 400-byte rows 64 -> 59 us).
+// Measured at a 56 GB table of 512-byte rows, step time with four plans in flight / on one stream: table loads and all stores
+// non-temporal 183 / 215 us (X rows of new vertices only: 191 / 222 us), loads cached and stores non-temporal 174 / 214 us,
+// both cached 194 / 242 us.
 
 FinishArgs finish_args(const zg_plan_t *p, bool present, const zg_plan_t *gate = nullptr, bool defer_completed = false)
 {
@@ -1393,8 +1386,8 @@ void step_feature_args(const zg_plan_t *p, RowArgs *gat, RowArgs *agg, int *vec)
         agg->x_dst = p->X();
         agg->ld_x = L.ld_out;
         agg->own = p->own();
-        agg->nt = one_pass_streams(p) ? 1 : 0;
     }
+    if (fused || one_pass) agg->nt = 1;
     *gat = gather_args(p, p->d_feat, p->ld_feat, L.feat_dim, p->X(), L.ld_out, (fused || one_pass) ? H - 1 : H, &v2);
     *vec = v1; // both tilings take the same vector width for the same dim and alignment
     gat->vec4 = agg->vec4 = *vec == 4 ? 1 : 0;
