@@ -465,24 +465,43 @@ def main():
     # the step's own two feature launches, replayed on the last step's state: the gather copies the frontier's rows, the
     # aggregation reads its input rows from the table and writes the other rows of X (those of the last hop's new vertices)
     t_gather = time_kernel(lambda: plan.replay_features(0))
-    t_agg = time_kernel(lambda: plan.replay_features(1))
-    n_new = nH - nHm1
+    t_agg_replay = time_kernel(lambda: plan.replay_features(1))
     one_pass = bool(plan.out.x_one_pass)
     row = 4 * cfg.dim
-    if one_pass:
-        # the gather copies the frontier's rows; the aggregation reads every distinct row its edges point to at least once
-        # (counted exactly, from the last step's block), writes the new vertices' rows into X, and writes the means
-        gather_rows = nHm1
-        distinct = int(torch.unique(plan.view_block(H - 1)[1][:EHm1]).numel())
-        csr = EHm1 * (4 + 4 + 1) + (nHm1 + 1) * 4  # sampled ids, local ids (written here), first-edge flags, row_ptr
-        bytes_agg = distinct * row + n_new * row + nHm1 * row + csr
-        bytes_agg_noreuse = EHm1 * row + n_new * row + nHm1 * row + csr  # every edge fetches its row
-    else:
-        # the gather copies every row of S_{H-1}; the aggregation reads every row of X at least once and writes the means
-        gather_rows = nH
-        csr = EHm1 * 4 + (nHm1 + 1) * 4
-        bytes_agg = nH * row + nHm1 * row + csr
-        bytes_agg_noreuse = EHm1 * row + nHm1 * row + csr
+
+    def aggregate_bytes():
+        """(compulsory bytes, bytes if every edge fetches its row) of the aggregation launch of the step just run."""
+        n_t, E_t, _, _ = plan.view_counts()
+        nH_, nHm1_, EHm1_ = int(n_t[H]), int(n_t[H - 1]), int(E_t[H - 1])
+        if one_pass:
+            # the aggregation reads every distinct row its edges point to at least once (counted exactly, from the
+            # step's block), writes the new vertices' rows into X, and writes the means
+            distinct = int(torch.unique(plan.view_block(H - 1)[1][:EHm1_]).numel())
+            csr = EHm1_ * (4 + 4 + 1) + (nHm1_ + 1) * 4  # sampled ids, local ids (written here), first-edge flags, row_ptr
+            return distinct * row + (nH_ - nHm1_) * row + nHm1_ * row + csr, EHm1_ * row + (nH_ - nHm1_) * row + nHm1_ * row + csr
+        # two passes: the aggregation reads every row of X at least once and writes the means
+        csr = EHm1_ * 4 + (nHm1_ + 1) * 4
+        return nH_ * row + nHm1_ * row + csr, EHm1_ * row + nHm1_ * row + csr
+
+    # The aggregation inside real steps: timed steps again on one stream, their kernels enqueued one by one with a pair of
+    # events around the aggregation launch (zg_step_timed); duration and bytes of every such launch, averaged per launch.
+    probes = min(K, args.kernel_reps)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(probes)]
+    for a, b in ev:  # (a first record creates the events' handles)
+        a.record(stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    sum_t = sum_b = sum_bn = 0.0
+    for i, (a, b) in enumerate(ev):
+        plan.step_timed(batches[Wm + i], keys[Wm + i], a, b)
+        torch.cuda.synchronize()
+        sum_t += a.elapsed_time(b) * 1e-3
+        ba, bn = aggregate_bytes()
+        sum_b += ba
+        sum_bn += bn
+    t_agg, bytes_agg, bytes_agg_noreuse = sum_t / probes, int(round(sum_b / probes)), int(round(sum_bn / probes))
+    n_new = nH - nHm1
+    gather_rows = nHm1 if one_pass else nH
     bytes_gather = gather_rows * (4 + 2 * row)
     kernels = {
         "gather": {"seconds": t_gather, "bytes": bytes_gather, "GBps": bytes_gather / t_gather / 1e9,
@@ -490,7 +509,9 @@ def main():
         # `bytes` is the compulsory figure; without cache reuse every edge fetches its row
         "aggregate": {"seconds": t_agg, "bytes": bytes_agg, "GBps": bytes_agg / t_agg / 1e9, "name": "k_aggregate",
                       "bytes_without_reuse": bytes_agg_noreuse, "GBps_without_reuse": bytes_agg_noreuse / t_agg / 1e9,
-                      "rows_read_per_edge": EHm1, "x_rows_written": n_new if one_pass else 0},
+                      "rows_read_per_edge": EHm1, "x_rows_written": n_new if one_pass else 0,
+                      "measured": f"inside {probes} of the timed steps (zg_step_timed: events around the launch), averaged per launch",
+                      "seconds_replayed_back_to_back": t_agg_replay},
     }
     dom = max(kernels, key=lambda k: kernels[k]["seconds"])
     roofline = {"bound": "hbm", "kernel": kernels[dom]["name"], "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,

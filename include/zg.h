@@ -326,6 +326,12 @@ int zg_calibration_copy(const void *d_src, void *d_dst, size_t bytes, void *stre
  * table and writes the remaining rows of X on the way.  Idempotent (the outputs are rewritten with the same values);
  * meant for timing the step's dominant kernels one by one.  Errors: ZG_EINVAL, ZG_ESTATE (no features bound), ZG_EHIP. */
 int zg_plan_replay_features(zg_plan_t *p, int32_t which, void *stream);
+/* zg_step with a stop-watch on its dominant kernel: the same step (same outputs, same mailbox and status bookkeeping),
+ * its kernels enqueued one by one as a ZG_PLAN_EAGER plan does instead of replaying the captured graph, and the caller's
+ * two events (hipEvent_t, created with timing enabled) recorded on `stream` right before and right after the
+ * aggregation launch (section 2.2, first GraphSAGE aggregation), so that their distance is that launch's duration
+ * inside a real step.  Errors: as zg_step; ZG_ESTATE if no feature table is bound. */
+int zg_step_timed(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream, void *event_before, void *event_after);
 
 #ifdef __cplusplus
 }

@@ -34,7 +34,7 @@ EXPORTS = ["zg_strerror", "zg_last_error", "zg_graph_create", "zg_graph_create_s
            "zg_plan_destroy", "zg_plan_bind_features", "zg_plan_outputs", "zg_step", "zg_gather",
            "zg_aggregate_mean", "zg_overflow_flag", "zg_overflow_clear", "zg_step_safe", "zg_plan_outputs_safe",
            "zg_step_status", "zg_envelope_model_graph", "zg_envelope_from_pilot", "zg_pilot_update", "zg_build_id",
-           "zg_calibration_copy", "zg_envelope_model_graph_static", "zg_plan_replay_features"]
+           "zg_calibration_copy", "zg_envelope_model_graph_static", "zg_plan_replay_features", "zg_step_timed"]
 
 
 class Envelope(C.Structure):
@@ -122,6 +122,7 @@ def lib() -> C.CDLL:
         L.zg_pilot_update.argtypes = [vp, P(i64), vp]
         L.zg_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.zg_plan_replay_features.argtypes = [vp, i32, vp]
+        L.zg_step_timed.argtypes = [vp, vp, u64, vp, vp, vp]
         for name in EXPORTS:
             if name not in ("zg_strerror", "zg_last_error", "zg_normal_quantile", "zg_build_id"):
                 getattr(L, name).restype = C.c_int
@@ -380,6 +381,12 @@ class Plan:
     def step(self, seeds, rng_key: int, stream=None) -> None:
         """Enqueue one mini-batch (seeds: int32 CUDA tensor of `batch` distinct ids); returns at once."""
         _check(lib().zg_step(self._h, seeds.data_ptr(), C.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), _stream_ptr(stream)))
+
+    def step_timed(self, seeds, rng_key: int, event_before, event_after, stream=None) -> None:
+        """One step enqueued kernel by kernel, the two events (torch.cuda.Event with timing, already recorded once so
+        that their handles exist) recorded right before and after its aggregation launch."""
+        _check(lib().zg_step_timed(self._h, seeds.data_ptr(), C.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), _stream_ptr(stream),
+                                   C.c_void_p(event_before.cuda_event), C.c_void_p(event_after.cuda_event)))
 
     def step_safe(self, seeds, rng_key: int, stream=None) -> None:
         """Replay the same mini-batch on the worst-case twin (plan made with PLAN_SAFE_TWIN)."""

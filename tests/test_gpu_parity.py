@@ -521,3 +521,40 @@ def test_graph_aware_size_model_matches_its_reference(oracle, i64, replace):
     compare_blocks(res, og.sample_blocks(pool.batch_for(29).numpy(), fan, 429, with_replacement=replace), "graph-aware envelope")
     with pytest.raises(zg.ZgError):
         zg.graph_model(zg.Graph.from_degree_histogram([1, 2], [10, 10]), (2,), 4)
+
+
+def test_timed_step_is_the_same_step_with_a_stop_watch(oracle):
+    # zg_step_timed enqueues the step's kernels one by one and records two events around the aggregation launch: same
+    # outputs as zg_step for the same (seeds, key), in any interleaving with graph replays, and a positive duration
+    g = W.rmat_graph(40_000, 900_000, 51)
+    og = to_host_graph(oracle, g)
+    dim = 64
+    feat = W.feature_table(40_000, dim, 5).cuda()
+    feat_h = feat.cpu().numpy()
+    dg = zg.Graph(g.offsets.cuda(), g.indices.cuda())
+    pool = W.SeedPool(g, 512, 8)
+    fan = (6, 5)
+    plan = zg.Plan(dg, fan, 512, zg.make_envelope(zg.ENV_MODEL), feat_dim=dim)
+    plan.bind_features(feat)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    b.record()
+    torch.cuda.synchronize()
+    for s in range(6):
+        seeds = pool.batch_for(s).cuda()
+        if s % 2:
+            plan.step_timed(seeds, 400 + s, a, b)
+            torch.cuda.synchronize()
+            assert 0.0 < a.elapsed_time(b) < 50.0  # milliseconds
+        else:
+            plan.step(seeds, 400 + s)
+        res = plan.read_step()
+        ref = og.sample_blocks(seeds.cpu().numpy(), fan, 400 + s)
+        compare_blocks(res, ref, f"step {s}")
+        compare_features(oracle, res, ref, feat_h, f"step {s}")
+    done, flags = plan.step_status()
+    assert done == 6 and flags == 0
+    # no feature table bound: refused
+    bare = zg.Plan(dg, fan, 512, zg.make_envelope(zg.ENV_MODEL), feat_dim=0)
+    with pytest.raises(zg.ZgError):
+        bare.step_timed(pool.batch_for(0).cuda(), 1, a, b)
