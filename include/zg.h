@@ -330,7 +330,8 @@ int zg_plan_replay_features(zg_plan_t *p, int32_t which, void *stream);
  * its kernels enqueued one by one as a ZG_PLAN_EAGER plan does instead of replaying the captured graph, and the caller's
  * two events (hipEvent_t, created with timing enabled) recorded on `stream` right before and right after the
  * aggregation launch (section 2.2, first GraphSAGE aggregation), so that their distance is that launch's duration
- * inside a real step.  Errors: as zg_step; ZG_ESTATE if no feature table is bound. */
+ * inside a real step.  Errors: as zg_step; ZG_ESTATE if no feature table is bound; ZG_EHIP if an event could not be
+ * recorded (the step is enqueued all the same and counts as a step of the plan). */
 int zg_step_timed(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream, void *event_before, void *event_after);
 
 #ifdef __cplusplus

@@ -1400,16 +1400,17 @@ bool features_ride_along(const zg_plan_t *p)
     return p->d_feat && p->lay.feat_dim > 0 && ((p->flags & ZG_PLAN_FUSED_INPUT) || x_written_by_aggregation(p));
 }
 
-// a whole step, in order, on one stream (captured once, or issued eagerly): the hop kernel's launches 0..H, then the
-// two feature launches.  With `gate` the kernels are those of gate's worst-case twin `p`, run on gate's inputs and
-// only if gate's step overflowed; `defer_completed` marks a plan whose gated twin follows in the same sequence.
 // zg_step_timed: events to record right before and right after the aggregation launch of the plan's own step
 struct StepProbe {
     hipEvent_t before, after;
+    hipError_t error; // what recording them returned (the step is enqueued either way)
 };
 
+// a whole step, in order, on one stream (captured once, or issued eagerly): the hop kernel's launches 0..H, then the
+// two feature launches.  With `gate` the kernels are those of gate's worst-case twin `p`, run on gate's inputs and
+// only if gate's step overflowed; `defer_completed` marks a plan whose gated twin follows in the same sequence.
 int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nullptr, bool defer_completed = false,
-                 const StepProbe *probe = nullptr)
+                 StepProbe *probe = nullptr)
 {
     const Layout &L = p->lay;
     const zg_graph_t *g = p->graph;
@@ -1489,14 +1490,14 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
         int rc = launch_gather(vec, gat, relabel_args(p, H - 1, true, gate), st);
         if (rc != ZG_OK) return rc;
     }
-    if (probe) ZG_HIP(hipEventRecord(probe->before, st));
+    if (probe) probe->error = hipEventRecord(probe->before, st);
     int rc = launch_aggregate(vec, agg, finish_args(p, true, gate, defer_completed), st);
-    if (rc == ZG_OK && probe) ZG_HIP(hipEventRecord(probe->after, st));
+    if (rc == ZG_OK && probe && probe->error == hipSuccess) probe->error = hipEventRecord(probe->after, st);
     return rc;
 }
 
 // the plan's step, followed - with ZG_PLAN_AUTO_FALLBACK - by its twin's step behind the device-side gate
-int enqueue_step(const zg_plan_t *p, hipStream_t st, const StepProbe *probe = nullptr)
+int enqueue_step(const zg_plan_t *p, hipStream_t st, StepProbe *probe = nullptr)
 {
     const bool autofb = (p->flags & ZG_PLAN_AUTO_FALLBACK) && p->twin;
     int rc = enqueue_body(p, st, nullptr, autofb, probe);
@@ -1691,7 +1692,7 @@ int zg_plan_outputs(const zg_plan_t *p, zg_outputs *o)
 
 // zg_step and zg_step_timed: fill the next mailbox slot, then replay the captured graph - or, for an eager plan and for
 // the timed variant, enqueue the step's kernels one by one
-static int issue_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream, const StepProbe *probe)
+static int issue_step(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *stream, StepProbe *probe)
 {
     if (!p || !d_seeds) return fail(ZG_EINVAL, "null argument");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1734,8 +1735,11 @@ int zg_step_timed(zg_plan_t *p, const int32_t *d_seeds, uint64_t rng_key, void *
 {
     if (!event_before || !event_after) return fail(ZG_EINVAL, "null argument");
     if (p && !(p->d_feat && p->lay.feat_dim > 0)) return fail(ZG_ESTATE, "no feature table bound: the step has no aggregation launch");
-    const StepProbe probe{static_cast<hipEvent_t>(event_before), static_cast<hipEvent_t>(event_after)};
-    return issue_step(p, d_seeds, rng_key, stream, &probe);
+    StepProbe probe{static_cast<hipEvent_t>(event_before), static_cast<hipEvent_t>(event_after), hipSuccess};
+    const int rc = issue_step(p, d_seeds, rng_key, stream, &probe);
+    if (rc == ZG_OK && probe.error != hipSuccess)
+        return fail(ZG_EHIP, std::string("hipEventRecord: ") + hipGetErrorString(probe.error) + " (the step itself is enqueued)");
+    return rc;
 }
 
 int zg_plan_replay_features(zg_plan_t *p, int32_t which, void *stream)
