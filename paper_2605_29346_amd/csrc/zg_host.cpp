@@ -35,23 +35,12 @@ RowTiling gather_tiling(int32_t dim, bool aligned16)
 RowTiling aggregate_tiling(int32_t dim, bool aligned16)
 {
     RowTiling t = gather_tiling(dim, aligned16);
-    // One (row, piece) pair per lane and turn of the lanes' loop.  Small workgroups, many of them, hide the staging of the
-    // block's edges best (measured at 128-float rows: 256 pairs per workgroup 86 us, 512 pairs 91, 1024 pairs 101), so the
-    // rows of a workgroup are the fewest that leave under 5 % of the lanes idle in the last turn - 8 rows of 32 pieces fill 256
-    // lanes exactly, one row of 150 pieces would leave 106 of 256 idle, five such rows fill 750 of 768 (600-float rows, four
-    // plans in flight: 71 -> 67 us per step) - within 1024 pairs.
-    uint32_t best = 1;
-    double best_idle = 2.0;
-    for (uint32_t r = 1; r <= 64 && (r == 1 || r * t.dimv <= 1024u); ++r) {
-        const uint32_t pairs = r * t.dimv, turns = (pairs + 255u) / 256u;
-        const double idle = (double)(turns * 256u - pairs) / (double)(turns * 256u);
-        if (idle < best_idle - 1e-9) {
-            best_idle = idle;
-            best = r;
-        }
-        if (idle < 0.05 && pairs >= 224u) break;
-    }
-    t.rows = best;
+    // one (row, piece) pair per lane: small workgroups, many of them, hide the staging of the block's edges best
+    // (measured at 128- and 600-float rows: 256 pairs per workgroup 86 / 41 us, 512 pairs 91 / 42, 1024 pairs 101 / 44).
+    // Filling the lanes better for widths that leave many idle (five 600-float rows = 750 pairs instead of one = 150 of 256
+    // lanes) was measured too: the kernel alone gets slower (55 -> 59 us), four plans in flight faster (77 -> 74 us per step),
+    // deeper sampling slower again - not kept.
+    t.rows = std::max<uint32_t>(1, std::min<uint32_t>(64, 256u / t.dimv));
     return t;
 }
 
