@@ -549,12 +549,13 @@ __device__ __forceinline__ uint32_t lowest_set_bits(uint32_t x, uint32_t q)
 // sampled edges.  A ticket first finds its rows' lengths k_i = min(F, deg) ("row lengths"; 256 rows at a time, held in
 // LDS), publishes both totals, takes its exclusive prefixes (wavefront 0 and wavefront 1, side by side), and then
 // writes S, the id map and row_ptr ("offsets scan") and samples its rows in passes of 1024 / G rows, one lane per
-// (row, slot) ("sample").  A ranking tile holds its bitmap words in registers (up to 8 per lane), adds the kept
+// (row, slot) ("sample").  A ranking tile holds its bitmap words in registers (up to WPL per lane: 8, or 16 in the
+// instantiation for sparse launches over very long bitmaps), adds the kept
 // bits to "seen" and clears the words.  Vertices ranked beyond the cap are dropped (no row, local id -1, not "seen")
 // and the hop's overflow bit is raised; the rows kept are a prefix of the row order, so the block stays consistent up
 // to the cap.  Launch H ranks only.  The launch's surplus workgroups (the grid is sized by the caps) find no ticket
 // and return.
-template <typename OffT>
+template <typename OffT, int WPL>
 __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel, IngestArgs ing, RowArgs gat)
 {
     __shared__ HopShared sh;
@@ -592,27 +593,28 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
     // ---- what this ticket's rows are
     uint32_t m;                       // rows of this ticket: old rows, or the tile's new vertices
     uint32_t lex = 0;                 // ranking tile: in-tile index of this lane's first new vertex
-    uint32_t nw[kHopMaxWordsPerLane]; // ranking tile: this lane's new vertices (bitmap bits that are not "seen")
+    uint32_t nw[WPL]; // ranking tile: this lane's new vertices (bitmap bits that are not "seen")
     uint32_t had = 0;                 // ... and which of its bitmap words were not empty
     const uint32_t r0 = ticket * R;   // old rows: the first row
     const uint32_t W = a.words_per_tile;
     const uint32_t wpl = W >= (uint32_t)kHopBlock ? W / (uint32_t)kHopBlock : 1u;
     const size_t w0 = old ? 0 : (size_t)(ticket - t_old) * W + (size_t)tid * wpl; // ranking tile: this lane's first word
 #pragma unroll
-    for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) nw[r] = 0u;
+    for (uint32_t r = 0; r < WPL; ++r) nw[r] = 0u;
     if (old) {
         m = n_old - r0 < R ? n_old - r0 : R;
     } else {
         const bool owner = W >= (uint32_t)kHopBlock || (uint32_t)tid < W;
         // the lane's words of the hop's bitmap, then - only where a word is not empty - the same words of "seen"
         // (wide loads: a lane's words are consecutive)
-        auto load_words = [&](const uint32_t *src, uint32_t (&x)[kHopMaxWordsPerLane]) {
-            if (wpl == 8) {
-                const uint4 p = *reinterpret_cast<const uint4 *>(src + w0), q = *reinterpret_cast<const uint4 *>(src + w0 + 4);
-                x[0] = p.x, x[1] = p.y, x[2] = p.z, x[3] = p.w, x[4] = q.x, x[5] = q.y, x[6] = q.z, x[7] = q.w;
-            } else if (wpl == 4) {
-                const uint4 p = *reinterpret_cast<const uint4 *>(src + w0);
-                x[0] = p.x, x[1] = p.y, x[2] = p.z, x[3] = p.w;
+        auto load_words = [&](const uint32_t *src, uint32_t (&x)[WPL]) {
+            if (wpl >= 4) {
+#pragma unroll
+                for (uint32_t q = 0; q < (uint32_t)WPL / 4u; ++q)
+                    if (4u * q < wpl) {
+                        const uint4 p = *reinterpret_cast<const uint4 *>(src + w0 + 4u * q);
+                        x[4 * q] = p.x, x[4 * q + 1] = p.y, x[4 * q + 2] = p.z, x[4 * q + 3] = p.w;
+                    }
             } else if (wpl == 2) {
                 const uint2 p = *reinterpret_cast<const uint2 *>(src + w0);
                 x[0] = p.x, x[1] = p.y;
@@ -622,19 +624,26 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
         };
         if (owner) load_words(a.bitmap_prev, nw);
 #pragma unroll
-        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r)
+        for (uint32_t r = 0; r < WPL; ++r)
             if (nw[r]) had |= 1u << r;
         if (had) {
-            uint32_t sn[kHopMaxWordsPerLane];
+            if (wpl >= 4) {
 #pragma unroll
-            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) sn[r] = 0u;
-            load_words(a.seen, sn);
-#pragma unroll
-            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) nw[r] &= ~sn[r];
+                for (uint32_t q = 0; q < (uint32_t)WPL / 4u; ++q)
+                    if (4u * q < wpl && ((had >> (4u * q)) & 0xFu)) {
+                        const uint4 sn = *reinterpret_cast<const uint4 *>(a.seen + w0 + 4u * q);
+                        nw[4 * q] &= ~sn.x, nw[4 * q + 1] &= ~sn.y, nw[4 * q + 2] &= ~sn.z, nw[4 * q + 3] &= ~sn.w;
+                    }
+            } else if (wpl == 2) {
+                const uint2 sn = *reinterpret_cast<const uint2 *>(a.seen + w0);
+                nw[0] &= ~sn.x, nw[1] &= ~sn.y;
+            } else {
+                nw[0] &= ~a.seen[w0];
+            }
         }
         uint32_t cnt = 0;
 #pragma unroll
-        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) cnt += __popc(nw[r]);
+        for (uint32_t r = 0; r < WPL; ++r) cnt += __popc(nw[r]);
         const uint32_t incl = wave_incl_scan(cnt, lane);
         if (lane == 63) sh.wsum[wave] = incl;
         __syncthreads();
@@ -661,7 +670,7 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
             const uint32_t c1 = c0 + kHopRows;
             uint32_t j = lex;
 #pragma unroll
-            for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) {
+            for (uint32_t r = 0; r < WPL; ++r) {
                 uint32_t x = nw[r];
                 const uint32_t pc = __popc(x);
                 if (j + pc <= c0 || j >= c1) { // all before this batch, or this batch is full: nothing to write
@@ -767,7 +776,7 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
         // ---- closing launch: ranks only
         uint32_t j = lex;
 #pragma unroll
-        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r) {
+        for (uint32_t r = 0; r < WPL; ++r) {
             uint32_t x = nw[r];
             while (x) {
                 const int b = __ffs((int)x) - 1;
@@ -797,7 +806,7 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
     if (had) {
         uint32_t left = lex < room ? room - lex : 0u; // how many of this lane's vertices are kept
 #pragma unroll
-        for (uint32_t r = 0; r < kHopMaxWordsPerLane; ++r)
+        for (uint32_t r = 0; r < WPL; ++r)
             if (had & (1u << r)) {
                 const uint32_t pc = __popc(nw[r]);
                 if (sampling && nw[r]) {
@@ -1478,10 +1487,18 @@ int enqueue_body(const zg_plan_t *p, hipStream_t st, const zg_plan_t *gate = nul
             ga.blocks = (uint32_t)((L.node_cap[H - 1] + ga.rows - 1) / ga.rows);
         }
         const unsigned grid = ha.blocks + ra.blocks + ia.blocks + ga.blocks;
-        if (g->offsets_dtype == ZG_I64)
-            hipLaunchKernelGGL(k_hop<int64_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
-        else
-            hipLaunchKernelGGL(k_hop<int32_t>, dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
+        const bool fat = ha.words_per_tile > (uint32_t)kHopMaxTileWords; // a sparse ranking launch over a very long bitmap
+        if (g->offsets_dtype == ZG_I64) {
+            if (fat)
+                hipLaunchKernelGGL((k_hop<int64_t, kHopFatWordsPerLane>), dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
+            else
+                hipLaunchKernelGGL((k_hop<int64_t, kHopMaxWordsPerLane>), dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
+        } else {
+            if (fat)
+                hipLaunchKernelGGL((k_hop<int32_t, kHopFatWordsPerLane>), dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
+            else
+                hipLaunchKernelGGL((k_hop<int32_t, kHopMaxWordsPerLane>), dim3(grid), dim3(kHopBlock), 0, st, ha, ra, ia, ga);
+        }
         ZG_HIP(hipGetLastError());
     }
     // the tail: {gather + relabel of the last hop} - unless both ride along elsewhere -, then {aggregation + end-of-step

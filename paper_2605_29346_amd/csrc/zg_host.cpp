@@ -230,7 +230,7 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
         // two chosen so that a tile holds about one sampling pass (1024 / G vertices) of new rows at the cap, within the
         // ticket budget and between 32 and 8192 words.
         const int64_t words = (V + 31) / 32;
-        L.bitmap_words = (int64_t)align_up((size_t)words, (size_t)kHopMaxTileWords);
+        L.bitmap_words = (int64_t)align_up((size_t)words, (size_t)kHopFatTileWords);
         for (int l = 0; l <= num_hops; ++l) {
             // The launch's tickets share one budget: workgroups beyond what the chip holds at once (two of 1024 lanes per
             // compute unit) only start when earlier ones have finished - a second round that doubles the launch's time.
@@ -241,7 +241,12 @@ static int compute_layout_one(const zg_graph_t *g, const int32_t *fanouts, int32
                 const int64_t budget = std::max<int64_t>(std::max<int64_t>(1, max_tickets / 2), max_tickets - fattest_old);
                 const int64_t want = std::max<int64_t>(1, std::min<int64_t>(budget, (L.node_cap[l] + T - 1) / T));
                 int64_t W = kHopMinTileWords;
-                while (W < kHopMaxTileWords && W * want < words) W *= 2;
+                // A launch that samples for few rows over a very long bitmap (its tile count is set by the rows, not by the
+                // budget) takes tiles of 16 words per lane: half the tickets, each still about one sampling pass of rows.
+                // (At 110 M vertices: 210 instead of 420 tickets in the launch that ranks hop 0's ~9 k discoveries, -2 to -4 %
+                // step time; the same for a launch at the ticket budget doubles its rows per ticket and costs +16 %.)
+                const int64_t max_words = (l < num_hops && want < budget) ? kHopFatTileWords : kHopMaxTileWords;
+                while (W < max_words && W * want < words) W *= 2;
                 L.tile_words[l] = (int32_t)W;
                 L.rank_tiles[l] = (words + W - 1) / W;
             }

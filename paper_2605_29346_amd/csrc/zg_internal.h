@@ -18,6 +18,8 @@ constexpr int kHopMaxTpt = 4;           // most consecutive tiles of frontier ro
 constexpr int kHopMaxWordsPerLane = 8;  // bitmap words a lane owns in a ranking tile (held in registers)
 constexpr int kHopMinTileWords = 32;    // smallest ranking tile: 32 words = 1024 vertices
 constexpr int kHopMaxTileWords = kHopBlock * kHopMaxWordsPerLane; // largest: 8192 words = 262144 vertices
+constexpr int kHopFatWordsPerLane = 16; // ... 16 in a launch whose tile count is set by its (few) rows, not by the ticket budget
+constexpr int kHopFatTileWords = kHopBlock * kHopFatWordsPerLane; // 16384 words = 524288 vertices
 constexpr int kSampleHashBits = 11;      // LDS dedup set of a sampling workgroup: 2048 slots for <= 1024 ids
 constexpr int kSampleHashSlots = 1 << kSampleHashBits;
 constexpr uint64_t kGatherStreamBytes = 160ull << 20; // gathered matrices above this size are copied with non-temporal accesses

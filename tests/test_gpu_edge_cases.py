@@ -106,6 +106,24 @@ def test_all_tile_variants_of_the_chained_scans(oracle, max_tickets):
     assert info.grid_sample[2] <= max(max_tickets, -(-info.node_cap[1] // 256)) + max(max_tickets, -(-words // 8192))
 
 
+def test_sparse_launch_over_a_long_bitmap_takes_16_words_per_lane(oracle):
+    # a handful of seeds on a 600 k-vertex graph: the launches that rank hop 0's and hop 1's few discoveries need one or two
+    # tickets for their rows, so their ranking tiles grow to 16384 words (16 per lane: the second instantiation of the
+    # hop kernel); the last tile reaches past the bitmap's last word into its zero padding
+    g = W.rmat_graph(600_000, 3_000_000, 17)
+    feat = W.feature_table(600_000, 8, 2)
+    og = to_host_graph(oracle, g)
+    pool = W.SeedPool(g, 6, 11)
+    plan = None
+    for s in range(3):
+        plan, res, ref = run_and_compare(oracle, g, feat, pool.batch_for(s).numpy(), (4, 3, 3), 70 + s, plan=plan, og=og,
+                                         env=zg.make_envelope(zg.ENV_MAX))
+    words = -(-600_000 // 32)
+    # launch 1: its old rows' tickets plus ranking tiles of 16384 words
+    assert plan.info.grid_sample[1] <= 1 + -(-words // 16384) + 1
+    assert ref.n[-1] > 6
+
+
 def test_randomised_configurations(oracle):
     # 40 random (graph, batch, hops, fanouts, feature width, envelope mode, replacement) draws, two steps each
     # (ZG_FUZZ_TRIALS runs more of them, ZG_FUZZ_SEED another sequence)

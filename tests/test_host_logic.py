@@ -261,3 +261,18 @@ def test_every_device_flag_reaches_the_per_step_word():
 def test_build_id_names_the_sources_in_the_tree():
     from paper_2605_29346_amd import build as zg_build
     assert zg.lib().zg_build_id().decode() == zg_build.source_id()
+
+
+def test_ranking_tiles_grow_to_16_words_per_lane_only_where_rows_not_the_budget_set_the_tile_count():
+    # 100 M vertices of degree 12 (3.125 M bitmap words), 4096 seeds, explicit caps: the launch that ranks hop 0's
+    # discoveries has rows for ~250 tickets, fewer than the budget allows: tiles of 16384 words (191 of them); the next
+    # launch is at the ticket budget and the closing launch only ranks: tiles of 8192 words (382)
+    g = zg.Graph.from_degree_histogram([12], [100_000_000])
+    caps = [4096, 16_000, 120_000, 500_000]
+    info = g.plan_query((15, 10, 5), 4096, zg.make_envelope(zg.ENV_EXPLICIT, node_caps=caps))
+    words = 100_000_000 // 32
+    t8, t16 = -(-words // 8192), -(-words // 16384)
+    assert info.grid_sample[0] == 4096 // 64                      # fanout 15: 16 lanes per row, 64 rows per ticket
+    assert info.grid_sample[1] == 4096 // 64 + t16                # fanout 10: 64 old rows per ticket + fat ranking tiles (255 tickets)
+    assert info.grid_sample[2] == -(-16_000 // 256) + t8          # fanout 5: two tiles of 128 old rows per ticket, to stay in the budget
+    assert info.grid_compact == t8
