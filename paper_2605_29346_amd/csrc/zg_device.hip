@@ -560,17 +560,43 @@ __global__ __launch_bounds__(kHopBlock, 8) void k_hop(HopArgs a, RelabelArgs rel
 {
     __shared__ HopShared sh;
     if (gate_closed(a.gate)) return;
-    if (blockIdx.x >= a.blocks) {
-        const uint32_t b = blockIdx.x - a.blocks;
-        if (b < rel.blocks)
-            relabel_block(rel, b);
-        else if (b < rel.blocks + ing.blocks)
-            ingest_block(ing, b - rel.blocks, sh.in);
-        else if (gat.vec4) // the closing launch may carry the copy of the frontier's feature rows (their ids are final by now)
-            gather_rows_block<4>(gat, b - rel.blocks - ing.blocks, sh.v);
-        else
-            gather_rows_block<1>(gat, b - rel.blocks - ing.blocks, sh.v);
-        return;
+    // Roles by workgroup index.  The closing launch may carry the copy of the frontier's feature rows (their ids are final
+    // by now): its copy workgroups alternate with the ticket workgroups at the head of the grid, so that the copy - bound by
+    // bandwidth - runs while the tickets - chains of dependent accesses - wait, instead of after them (tickets are handed
+    // out in start order, whichever workgroups ask).  Then the remaining tickets, the relabel and ingest roles, the
+    // remaining copy workgroups.
+    {
+        uint32_t b = blockIdx.x;
+        const uint32_t pairs = a.blocks < gat.blocks ? a.blocks : gat.blocks; // (0 without the copy role)
+        bool ticket_role;
+        uint32_t copy_block = 0xFFFFFFFFu;
+        if (b < 2u * pairs) {
+            ticket_role = (b & 1u) == 0u;
+            if (!ticket_role) copy_block = b >> 1;
+        } else {
+            b -= 2u * pairs;
+            ticket_role = b < a.blocks - pairs;
+            if (!ticket_role) {
+                b -= a.blocks - pairs;
+                if (b < rel.blocks) {
+                    relabel_block(rel, b);
+                    return;
+                }
+                b -= rel.blocks;
+                if (b < ing.blocks) {
+                    ingest_block(ing, b, sh.in);
+                    return;
+                }
+                copy_block = pairs + (b - ing.blocks);
+            }
+        }
+        if (!ticket_role) {
+            if (gat.vec4)
+                gather_rows_block<4>(gat, copy_block, sh.v);
+            else
+                gather_rows_block<1>(gat, copy_block, sh.v);
+            return;
+        }
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Drmb *d = a.drmb;
