@@ -122,6 +122,16 @@ def test_sparse_launch_over_a_long_bitmap_takes_16_words_per_lane(oracle):
     # launch 1: its old rows' tickets plus ranking tiles of 16384 words
     assert plan.info.grid_sample[1] <= 1 + -(-words // 16384) + 1
     assert ref.n[-1] > 6
+    # the same launches with a cap that cuts into the rows a 16-word tile ranks: flagged, and the rows kept are a prefix
+    seeds = pool.batch_for(2).numpy()
+    caps = [0, ref.n[1], ref.n[2] - 3, ref.n[3]]
+    tight = zg.Plan(zg.Graph(g.offsets.cuda(), g.indices.cuda()), (4, 3, 3), 6, zg.make_envelope(zg.ENV_EXPLICIT, node_caps=caps), feat_dim=0)
+    tight.step(torch.as_tensor(seeds).cuda(), 72)
+    torch.cuda.synchronize()
+    n, E, n_exact, flags = [t.cpu().numpy() for t in tight.view_counts()]
+    assert int(flags[0]) & zg.FLAG_HOP_OVERFLOW(1)
+    assert n[2] == ref.n[2] - 3 and n_exact[2] == ref.n[2]
+    assert np.array_equal(tight.view_S()[: n[2]].cpu().numpy(), ref.S[: n[2]])
 
 
 def test_randomised_configurations(oracle):
